@@ -1,0 +1,636 @@
+// Host side of libxsv: context, argument validation, state machine, launch sequencing.
+// Every step of the path runs in the kernels of attend.hip / score_select.hip / requant.hip; this
+// file only decides WHICH launches a step needs (the cache lengths are known on the host: they
+// depend on token counts alone) and owns the device memory.
+#include "../../include/xsv.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <type_traits>
+#include <vector>
+
+#include "xsv_internal.h"
+
+using namespace xsv;
+
+namespace {
+
+enum Phase { kIdle = 0, kAttended = 1, kScored = 2 };
+
+struct LayerState {
+  int T = 0;        // cached tokens
+  int frames = 0;   // frames seen
+  int buf = 0;      // buffer holding the cache
+  int phase = kIdle;
+  int pending_Tn = 0;   // keep length decided by score_prune
+  int last_P = 0;       // scores computed by the last score_prune (0 if none)
+  int last_keep = 0;
+};
+
+}  // namespace
+
+struct xsv_ctx {
+  xsv_config cfg;
+  hipStream_t stream;
+  CachePool pool;
+  Workspace ws;
+  std::vector<LayerState> layers;
+  std::vector<void*> allocs;
+  int splits_single = 0, splits_batched = 0;
+  int max_splits = 1;
+  size_t part_rows = 0;  // rows the partial-output workspace holds
+  int n_cu = 256;
+  bool broken = false;
+};
+
+namespace {
+
+int round_up(int a, int b) { return (a + b - 1) / b * b; }
+
+bool tensor_ok(const xsv_tensor& t) {
+  return t.ptr != nullptr && t.stride_token >= kD && t.stride_head >= 0 &&
+         (reinterpret_cast<uintptr_t>(t.ptr) % 16 == 0) && t.stride_token % 8 == 0 && t.stride_head % 8 == 0;
+}
+
+int hip_fail(xsv_ctx* ctx) {
+  if (ctx) ctx->broken = true;
+  return XSV_ERR_HIP;
+}
+
+template <typename T>
+int dev_alloc(xsv_ctx* ctx, T** out, size_t count, bool zero) {
+  void* p = nullptr;
+  const size_t bytes = std::max<size_t>(count * sizeof(T), 256);
+  if (hipMalloc(&p, bytes) != hipSuccess) {
+    (void)hipGetLastError();
+    return XSV_ERR_OOM;
+  }
+  ctx->allocs.push_back(p);
+  if (zero && hipMemsetAsync(p, 0, bytes, ctx->stream) != hipSuccess) return XSV_ERR_HIP;
+  *out = static_cast<T*>(p);
+  return XSV_OK;
+}
+
+void free_all(xsv_ctx* ctx) {
+  for (void* p : ctx->allocs) (void)hipFree(p);
+  ctx->allocs.clear();
+}
+
+// What a step does to the cache length (paper Sec. 3.2: prune once T exceeds the budget; first and
+// current frames always stay).  Pure token counting — known on the host without reading the GPU.
+struct PrunePlan {
+  int T;         // length after the append
+  int T_first, T_cur, P, k;
+  bool prune;    // keep list differs from "everything"
+  bool score;    // scores are needed (0 < k < P)
+  int Tn;        // keep length
+};
+
+PrunePlan plan_for(const xsv_config& c, const LayerState& L) {
+  PrunePlan p{};
+  const int n = c.tokens_per_frame;
+  p.T = L.T + n;
+  p.T_first = n;
+  p.T_cur = n;
+  p.prune = !(c.budget == 0 || p.T <= c.budget || L.frames == 0);
+  if (!p.prune) {
+    p.P = 0; p.k = 0; p.score = false; p.Tn = p.T;
+    return p;
+  }
+  p.P = p.T - p.T_first - p.T_cur;
+  p.k = std::min(std::max(0, c.budget - p.T_first - p.T_cur), p.P);
+  p.score = p.k > 0 && p.k < p.P;
+  p.Tn = p.T_first + p.k + p.T_cur;
+  return p;
+}
+
+int choose_splits(const xsv_ctx* ctx, int n_layers, int Tc, int requested) {
+  const xsv_config& c = ctx->cfg;
+  const int n_tiles = (Tc + kTile - 1) / kTile + (c.tokens_per_frame + kTile - 1) / kTile;
+  int s = requested;
+  if (s <= 0) {
+    const int wgs = ((c.tokens_per_frame + 127) / 128) * c.n_heads * n_layers;
+    // aim at ~2 workgroups per compute unit, never ranges shorter than 8 tiles
+    s = (2 * ctx->n_cu + wgs - 1) / wgs;
+    s = std::min(s, std::max(1, n_tiles / 8));
+  }
+  const size_t rows_per_split = (size_t)n_layers * c.n_heads * c.tokens_per_frame;
+  s = std::max(1, std::min({s, ctx->max_splits, n_tiles, (int)(ctx->part_rows / rows_per_split)}));
+  return s;
+}
+
+int fill_batch(xsv_ctx* ctx, Batch& b, int layer0, int n_layers, const xsv_tensor* q, const xsv_tensor* k,
+               const xsv_tensor* v, void* const* out) {
+  std::memset(&b, 0, sizeof(b));
+  b.n_layers = n_layers;
+  b.layer0 = layer0;
+  for (int i = 0; i < n_layers; ++i) {
+    if (ctx->layers[layer0 + i].buf) b.bufsel |= 1u << i;
+    if (q) {
+      if (!tensor_ok(q[i]) || q[i].stride_head != q[0].stride_head || q[i].stride_token != q[0].stride_token) return XSV_ERR_ARG;
+      b.q[i] = static_cast<const uint16_t*>(q[i].ptr);
+    }
+    if (k) {
+      if (!tensor_ok(k[i]) || k[i].stride_head != k[0].stride_head || k[i].stride_token != k[0].stride_token) return XSV_ERR_ARG;
+      b.k[i] = static_cast<const uint16_t*>(k[i].ptr);
+    }
+    if (v) {
+      if (!tensor_ok(v[i]) || v[i].stride_head != v[0].stride_head || v[i].stride_token != v[0].stride_token) return XSV_ERR_ARG;
+      b.v[i] = static_cast<const uint16_t*>(v[i].ptr);
+    }
+    if (out) {
+      if (out[i] == nullptr || reinterpret_cast<uintptr_t>(out[i]) % 16 != 0) return XSV_ERR_ARG;
+      b.out[i] = static_cast<uint16_t*>(out[i]);
+    }
+  }
+  if (q) { b.q_sh = q[0].stride_head; b.q_st = q[0].stride_token; }
+  if (k) { b.k_sh = k[0].stride_head; b.k_st = k[0].stride_token; }
+  if (v) { b.v_sh = v[0].stride_head; b.v_st = v[0].stride_token; }
+  return XSV_OK;
+}
+
+// The three stages for layers [layer0, layer0 + n_layers), which must be in step with each other.
+int do_attend(xsv_ctx* ctx, int layer0, int n_layers, const xsv_tensor* q, const xsv_tensor* k, const xsv_tensor* v,
+              void* const* out, int splits_req) {
+  AttendArgs a{};
+  int rc = fill_batch(ctx, a.b, layer0, n_layers, q, k, v, out);
+  if (rc != XSV_OK) return rc;
+  a.pool = ctx->pool;
+  a.ws = ctx->ws;
+  a.Tc = ctx->layers[layer0].T;
+  a.n = ctx->cfg.tokens_per_frame;
+  a.n_splits = choose_splits(ctx, n_layers, a.Tc, splits_req);
+  a.qscale = ctx->cfg.softmax_scale * 1.4426950408889634f;
+  if (launch_attend(a, ctx->stream) != hipSuccess) return hip_fail(ctx);
+  for (int i = 0; i < n_layers; ++i) ctx->layers[layer0 + i].phase = kAttended;
+  return XSV_OK;
+}
+
+int do_score_prune(xsv_ctx* ctx, int layer0, int n_layers, const xsv_tensor* q) {
+  const PrunePlan p = plan_for(ctx->cfg, ctx->layers[layer0]);
+  int32_t* keep = ctx->ws.keep + (size_t)layer0 * ctx->ws.scores_stride;
+  if (!p.prune) {
+    if (launch_fill_keep(keep, ctx->ws.scores_stride, n_layers, p.T, 0, 0, true, ctx->stream) != hipSuccess) return hip_fail(ctx);
+  } else if (!p.score) {
+    // k == 0: first ∪ current;  k == P: everything (cannot happen once T > budget, kept for completeness)
+    if (launch_fill_keep(keep, ctx->ws.scores_stride, n_layers, p.T_first, p.P, p.T_cur, p.k == p.P, ctx->stream) != hipSuccess)
+      return hip_fail(ctx);
+  } else {
+    ScoreArgs s{};
+    int rc = fill_batch(ctx, s.b, layer0, n_layers, q, nullptr, nullptr, nullptr);
+    if (rc != XSV_OK) return rc;
+    s.pool = ctx->pool;
+    s.ws = ctx->ws;
+    s.Tc = ctx->layers[layer0].T;
+    s.n = ctx->cfg.tokens_per_frame;
+    s.n_special = ctx->cfg.n_special;
+    s.pool_size = ctx->cfg.pool_size;
+    s.T_first = p.T_first;
+    s.P = p.P;
+    s.k_plain = nullptr;
+    if (launch_pool_query(s, ctx->stream) != hipSuccess) return hip_fail(ctx);
+    if (launch_score(s, ctx->stream) != hipSuccess) return hip_fail(ctx);
+    SelectArgs sel{};
+    sel.scores = ctx->ws.scores + (size_t)layer0 * ctx->ws.scores_stride;
+    sel.keep = keep;
+    sel.scores_stride = sel.keep_stride = ctx->ws.scores_stride;
+    sel.n_layers = n_layers;
+    sel.P = p.P; sel.k = p.k; sel.T_first = p.T_first; sel.T_cur = p.T_cur;
+    if (launch_select(sel, ctx->stream) != hipSuccess) return hip_fail(ctx);
+  }
+  for (int i = 0; i < n_layers; ++i) {
+    LayerState& L = ctx->layers[layer0 + i];
+    L.phase = kScored;
+    L.pending_Tn = p.Tn;
+    L.last_P = p.score ? p.P : 0;
+    L.last_keep = p.Tn;
+  }
+  return XSV_OK;
+}
+
+int do_quantize(xsv_ctx* ctx, int layer0, int n_layers, const xsv_tensor* k, const xsv_tensor* v) {
+  RequantArgs r{};
+  int rc = fill_batch(ctx, r.b, layer0, n_layers, nullptr, k, v, nullptr);
+  if (rc != XSV_OK) return rc;
+  r.pool = ctx->pool;
+  r.ws = ctx->ws;
+  r.Tc = ctx->layers[layer0].T;
+  r.n = ctx->cfg.tokens_per_frame;
+  r.Tn = ctx->layers[layer0].pending_Tn;
+  r.frame_id = ctx->layers[layer0].frames;
+  if (launch_requant(r, ctx->stream) != hipSuccess) return hip_fail(ctx);
+  for (int i = 0; i < n_layers; ++i) {
+    LayerState& L = ctx->layers[layer0 + i];
+    L.T = r.Tn;
+    L.frames += 1;
+    L.buf ^= 1;
+    L.phase = kIdle;
+  }
+  return XSV_OK;
+}
+
+int check_layer(xsv_ctx* ctx, int layer) {
+  if (!ctx) return XSV_ERR_ARG;
+  if (ctx->broken) return XSV_ERR_HIP;
+  if (layer < 0 || layer >= ctx->cfg.n_layers) return XSV_ERR_ARG;
+  return XSV_OK;
+}
+
+int check_capacity(xsv_ctx* ctx, int layer) {
+  // the cache must hold what the step retains; only an unbounded cache can run out of room
+  if (plan_for(ctx->cfg, ctx->layers[layer]).Tn > ctx->pool.Tcap) return XSV_ERR_STATE;
+  return XSV_OK;
+}
+
+}  // namespace
+
+// device temporaries → host copies for the export and the stateless entry points
+namespace {
+struct Temp {
+  std::vector<void*> ptrs;
+  ~Temp() { for (void* p : ptrs) (void)hipFree(p); }
+  template <typename T> T* get(size_t count) {
+    void* p = nullptr;
+    if (hipMalloc(&p, std::max<size_t>(count * sizeof(T), 256)) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+    ptrs.push_back(p);
+    return static_cast<T*>(p);
+  }
+};
+}  // namespace
+
+extern "C" {
+
+const char* xsv_strerror(int code) {
+  switch (code) {
+    case XSV_OK: return "ok";
+    case XSV_ERR_ARG: return "invalid argument";
+    case XSV_ERR_UNSUPPORTED: return "configuration not supported by this build";
+    case XSV_ERR_OOM: return "device allocation failed";
+    case XSV_ERR_STATE: return "call order violated or layers out of step";
+    case XSV_ERR_HIP: return "HIP call failed";
+    default: return "unknown error";
+  }
+}
+
+int xsv_create(const xsv_config* cfg, void* hip_stream, xsv_ctx** out) {
+  if (!cfg || !out) return XSV_ERR_ARG;
+  *out = nullptr;
+  xsv_config c = *cfg;
+  if (c.n_layers < 1 || c.n_heads < 1 || c.tokens_per_frame < 1 || c.n_special < 0 || c.n_special > c.tokens_per_frame ||
+      c.budget < 0 || c.pool_size < 1 || !(c.softmax_scale >= 0.0f) || !std::isfinite(c.softmax_scale))
+    return XSV_ERR_ARG;
+  if (c.kv_bits != 2 && c.kv_bits != 4 && c.kv_bits != 16) return XSV_ERR_ARG;
+  if (c.head_dim != kD) return XSV_ERR_UNSUPPORTED;
+  if (c.kv_bits == 16) c.group_size = 64;
+  if (c.group_size != 32 && c.group_size != 64) return c.group_size > 0 ? XSV_ERR_UNSUPPORTED : XSV_ERR_ARG;
+  if (c.budget == 0 && c.max_frames < 1) return XSV_ERR_ARG;
+  if (c.softmax_scale == 0.0f) c.softmax_scale = 1.0f / std::sqrt((float)c.head_dim);
+  const long long n = c.tokens_per_frame;
+  // after a step the cache holds at most max(budget, first + current) tokens
+  const long long cap_tokens = c.budget > 0 ? std::max<long long>(c.budget, 2 * n) : n * c.max_frames;
+  if (cap_tokens > (1ll << 24) || (long long)c.n_heads * c.n_layers > (1 << 16)) return XSV_ERR_UNSUPPORTED;
+
+  xsv_ctx* ctx = new (std::nothrow) xsv_ctx;
+  if (!ctx) return XSV_ERR_OOM;
+  ctx->cfg = c;
+  ctx->stream = static_cast<hipStream_t>(hip_stream);
+  ctx->layers.resize(c.n_layers);
+  int dev = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) {
+    delete ctx;
+    return XSV_ERR_HIP;
+  }
+  ctx->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+
+  CachePool& p = ctx->pool;
+  std::memset(&p, 0, sizeof(p));
+  p.L = c.n_layers; p.H = c.n_heads; p.bits = c.kv_bits; p.G = c.group_size;
+  p.Tcap = round_up((int)cap_tokens, kTile);
+  const size_t slabs = 2 * (size_t)c.n_layers;
+  int rc = XSV_OK;
+  auto A = [&](auto** ptr, size_t count, bool zero) { if (rc == XSV_OK) rc = dev_alloc(ctx, ptr, count, zero); };
+  // zero-filled: padding rows of a ragged last block are read (masked) by the attention kernel
+  A(&p.kc, slabs * p.code_slab(), true);
+  A(&p.vc, slabs * p.code_slab(), true);
+  if (c.kv_bits != 16) {
+    A(&p.ks, slabs * p.kparam_slab(), true);
+    A(&p.kz, slabs * p.kparam_slab(), true);
+    A(&p.vs, slabs * p.vparam_slab(), true);
+    A(&p.vz, slabs * p.vparam_slab(), true);
+  }
+  A(&p.tok_frame, slabs * p.tok_slab(), true);
+  A(&p.tok_index, slabs * p.tok_slab(), true);
+
+  Workspace& w = ctx->ws;
+  std::memset(&w, 0, sizeof(w));
+  w.scores_stride = p.Tcap + (int)n;
+  w.qpart_rows = (int)((n + 127) / 128) * c.n_heads;
+  A(&w.scores, (size_t)c.n_layers * w.scores_stride, true);
+  A(&w.keep, (size_t)c.n_layers * w.scores_stride, true);
+  A(&w.qpart, (size_t)c.n_layers * w.qpart_rows * kD, true);
+  // partial attention outputs: up to 16 key ranges for one layer, or 2 per layer when batched
+  ctx->max_splits = 16;
+  const size_t part_rows = (size_t)std::max(16, 2 * std::min(c.n_layers, kMaxBatch)) * c.n_heads * n;
+  ctx->part_rows = part_rows;
+  A(&w.attn_o, part_rows * kD, false);
+  A(&w.attn_ml, part_rows * 2, false);
+  if (rc == XSV_OK && hipStreamSynchronize(ctx->stream) != hipSuccess) rc = XSV_ERR_HIP;
+  if (rc != XSV_OK) {
+    free_all(ctx);
+    delete ctx;
+    return rc;
+  }
+  *out = ctx;
+  return XSV_OK;
+}
+
+int xsv_destroy(xsv_ctx* ctx) {
+  if (!ctx) return XSV_OK;
+  (void)hipStreamSynchronize(ctx->stream);
+  free_all(ctx);
+  delete ctx;
+  return XSV_OK;
+}
+
+int xsv_reset(xsv_ctx* ctx) {
+  if (!ctx) return XSV_ERR_ARG;
+  if (ctx->broken) return XSV_ERR_HIP;
+  for (LayerState& L : ctx->layers) L = LayerState();
+  return XSV_OK;
+}
+
+int xsv_set_attend_splits(xsv_ctx* ctx, int per_layer_calls, int batched_calls) {
+  if (!ctx || per_layer_calls < 0 || per_layer_calls > 16 || batched_calls < 0 || batched_calls > 16) return XSV_ERR_ARG;
+  ctx->splits_single = per_layer_calls;
+  ctx->splits_batched = batched_calls;
+  return XSV_OK;
+}
+
+int xsv_dequant_attend(xsv_ctx* ctx, int layer, xsv_tensor q, xsv_tensor k_new, xsv_tensor v_new, void* out) {
+  int rc = check_layer(ctx, layer);
+  if (rc != XSV_OK) return rc;
+  if (ctx->layers[layer].phase != kIdle) return XSV_ERR_STATE;
+  if ((rc = check_capacity(ctx, layer)) != XSV_OK) return rc;
+  void* outs[1] = {out};
+  return do_attend(ctx, layer, 1, &q, &k_new, &v_new, outs, ctx->splits_single);
+}
+
+int xsv_score_prune(xsv_ctx* ctx, int layer, xsv_tensor q) {
+  int rc = check_layer(ctx, layer);
+  if (rc != XSV_OK) return rc;
+  if (ctx->layers[layer].phase != kAttended) return XSV_ERR_STATE;
+  if (!tensor_ok(q)) return XSV_ERR_ARG;
+  return do_score_prune(ctx, layer, 1, &q);
+}
+
+int xsv_quantize(xsv_ctx* ctx, int layer, xsv_tensor k_new, xsv_tensor v_new) {
+  int rc = check_layer(ctx, layer);
+  if (rc != XSV_OK) return rc;
+  if (ctx->layers[layer].phase != kScored) return XSV_ERR_STATE;
+  return do_quantize(ctx, layer, 1, &k_new, &v_new);
+}
+
+int xsv_step(xsv_ctx* ctx, int layer, xsv_tensor q, xsv_tensor k_new, xsv_tensor v_new, void* out) {
+  int rc = xsv_dequant_attend(ctx, layer, q, k_new, v_new, out);
+  if (rc != XSV_OK) return rc;
+  if ((rc = xsv_score_prune(ctx, layer, q)) != XSV_OK) return rc;
+  return xsv_quantize(ctx, layer, k_new, v_new);
+}
+
+int xsv_step_all_layers(xsv_ctx* ctx, const xsv_tensor* q, const xsv_tensor* k_new, const xsv_tensor* v_new,
+                        void* const* out) {
+  if (!ctx || !q || !k_new || !v_new || !out) return XSV_ERR_ARG;
+  if (ctx->broken) return XSV_ERR_HIP;
+  const int L = ctx->cfg.n_layers;
+  if (L > kMaxBatch) return XSV_ERR_UNSUPPORTED;
+  for (int l = 0; l < L; ++l) {
+    const LayerState& a = ctx->layers[l];
+    if (a.phase != kIdle || a.T != ctx->layers[0].T || a.frames != ctx->layers[0].frames) return XSV_ERR_STATE;
+  }
+  int rc = check_capacity(ctx, 0);
+  if (rc != XSV_OK) return rc;
+  if ((rc = do_attend(ctx, 0, L, q, k_new, v_new, out, ctx->splits_batched)) != XSV_OK) return rc;
+  if ((rc = do_score_prune(ctx, 0, L, q)) != XSV_OK) return rc;
+  return do_quantize(ctx, 0, L, k_new, v_new);
+}
+
+int xsv_cache_len(xsv_ctx* ctx, int layer, int32_t* T) {
+  int rc = check_layer(ctx, layer);
+  if (rc != XSV_OK) return rc;
+  if (!T) return XSV_ERR_ARG;
+  *T = ctx->layers[layer].T;
+  return XSV_OK;
+}
+
+
+int xsv_cache_export(xsv_ctx* ctx, int layer, uint8_t* k_codes, float* k_scale, float* k_zero, uint8_t* v_codes,
+                     float* v_scale, float* v_zero, uint16_t* k_bf16, uint16_t* v_bf16, int32_t* token_frame,
+                     int32_t* token_index) {
+  int rc = check_layer(ctx, layer);
+  if (rc != XSV_OK) return rc;
+  const LayerState& L = ctx->layers[layer];
+  if (L.phase != kIdle) return XSV_ERR_STATE;
+  const xsv_config& c = ctx->cfg;
+  const bool quant = c.kv_bits != 16;
+  if (!quant && (k_codes || k_scale || k_zero || v_codes || v_scale || v_zero)) return XSV_ERR_ARG;
+  const int T = L.T, H = c.n_heads, G = c.group_size;
+  if (T == 0) return XSV_OK;
+  const size_t n_el = (size_t)H * T * kD, n_kp = (size_t)H * ((T + G - 1) / G) * kD, n_vp = (size_t)H * T * (kD / G);
+  Temp tmp;
+  UnpackArgs u{};
+  u.pool = ctx->pool; u.buf = L.buf; u.layer = layer; u.T = T;
+  bool ok = true;
+  auto want = [&](auto*& dev, const void* host, size_t count) {
+    using P = std::remove_reference_t<decltype(dev)>;
+    dev = nullptr;
+    if (host) { dev = tmp.get<std::remove_pointer_t<P>>(count); ok = ok && dev != nullptr; }
+  };
+  want(u.k_codes, k_codes, n_el); want(u.v_codes, v_codes, n_el);
+  want(u.k_scale, k_scale, n_kp); want(u.k_zero, k_zero, n_kp);
+  want(u.v_scale, v_scale, n_vp); want(u.v_zero, v_zero, n_vp);
+  want(u.k_bf16, k_bf16, n_el); want(u.v_bf16, v_bf16, n_el);
+  if (!ok) return XSV_ERR_OOM;
+  if (launch_unpack(u, ctx->stream) != hipSuccess) return hip_fail(ctx);
+  bool good = true;
+  auto back = [&](void* host, const void* dev, size_t bytes) {
+    if (host && good) good = hipMemcpyAsync(host, dev, bytes, hipMemcpyDeviceToHost, ctx->stream) == hipSuccess;
+  };
+  back(k_codes, u.k_codes, n_el); back(v_codes, u.v_codes, n_el);
+  back(k_scale, u.k_scale, n_kp * 4); back(k_zero, u.k_zero, n_kp * 4);
+  back(v_scale, u.v_scale, n_vp * 4); back(v_zero, u.v_zero, n_vp * 4);
+  back(k_bf16, u.k_bf16, n_el * 2); back(v_bf16, u.v_bf16, n_el * 2);
+  const LayerCache lc = layer_cache(ctx->pool, L.buf, layer);
+  back(token_frame, lc.tok_frame, (size_t)T * 4);
+  back(token_index, lc.tok_index, (size_t)T * 4);
+  if (!good || hipStreamSynchronize(ctx->stream) != hipSuccess) return hip_fail(ctx);
+  return XSV_OK;
+}
+
+int xsv_cache_import(xsv_ctx* ctx, int layer, int32_t T, int32_t frames_seen, const uint8_t* k_codes,
+                     const float* k_scale, const float* k_zero, const uint8_t* v_codes, const float* v_scale,
+                     const float* v_zero, const uint16_t* k_bf16, const uint16_t* v_bf16, const int32_t* token_frame,
+                     const int32_t* token_index) {
+  int rc = check_layer(ctx, layer);
+  if (rc != XSV_OK) return rc;
+  LayerState& L = ctx->layers[layer];
+  const xsv_config& c = ctx->cfg;
+  const CachePool& p = ctx->pool;
+  if (L.phase != kIdle) return XSV_ERR_STATE;
+  if (T < 0 || T > p.Tcap || frames_seen < 0 || (T > 0 && frames_seen < 1) || (T > 0 && T < c.tokens_per_frame)) return XSV_ERR_ARG;
+  const bool quant = c.kv_bits != 16;
+  if (T > 0) {
+    if (quant && (!k_codes || !k_scale || !k_zero || !v_codes || !v_scale || !v_zero)) return XSV_ERR_ARG;
+    if (!quant && (!k_bf16 || !v_bf16)) return XSV_ERR_ARG;
+    if (!token_frame || !token_index) return XSV_ERR_ARG;
+  }
+  const int H = c.n_heads, G = c.group_size, bits = c.kv_bits;
+  const LayerCache lc = layer_cache(p, L.buf, layer);
+  if (hipStreamSynchronize(ctx->stream) != hipSuccess) return hip_fail(ctx);
+  // pack on the host into the library's private layout (layout marshalling only)
+  const size_t row_bytes = p.code_row_bytes();
+  std::vector<uint8_t> kc((size_t)H * p.Tcap * row_bytes, 0), vc((size_t)H * p.Tcap * row_bytes, 0);
+  const int ng = (T + G - 1) / G;
+  for (int h = 0; h < H; ++h)
+    for (int t = 0; t < T; ++t)
+      for (int ch = 0; ch < kD; ++ch) {
+        const size_t src = ((size_t)h * T + t) * kD + ch;
+        if (quant) {
+          const size_t kbit = (size_t)ch * bits, vbit = (size_t)(t % kTile) * bits;
+          kc[((size_t)h * p.Tcap + t) * row_bytes + kbit / 8] |= (uint8_t)((k_codes[src] & ((1 << bits) - 1)) << (kbit % 8));
+          vc[((size_t)h * p.Tcap + (size_t)(t / kTile) * kTile + ch) * row_bytes + vbit / 8] |=
+              (uint8_t)((v_codes[src] & ((1 << bits) - 1)) << (vbit % 8));
+        } else {
+          std::memcpy(&kc[((size_t)h * p.Tcap + t) * row_bytes + ch * 2], &k_bf16[src], 2);
+          std::memcpy(&vc[((size_t)h * p.Tcap + (size_t)(t / kTile) * kTile + ch) * row_bytes + (t % kTile) * 2], &v_bf16[src], 2);
+        }
+      }
+  bool good = hipMemcpy(lc.kc, kc.data(), kc.size(), hipMemcpyHostToDevice) == hipSuccess &&
+              hipMemcpy(lc.vc, vc.data(), vc.size(), hipMemcpyHostToDevice) == hipSuccess;
+  if (quant && T > 0) {
+    std::vector<float> ks(p.kparam_slab(), 0.f), kz(p.kparam_slab(), 0.f), vs(p.vparam_slab(), 0.f), vz(p.vparam_slab(), 0.f);
+    for (int h = 0; h < H; ++h) {
+      for (int g = 0; g < ng; ++g)
+        for (int ch = 0; ch < kD; ++ch) {
+          ks[((size_t)h * (p.Tcap / G) + g) * kD + ch] = k_scale[((size_t)h * ng + g) * kD + ch];
+          kz[((size_t)h * (p.Tcap / G) + g) * kD + ch] = k_zero[((size_t)h * ng + g) * kD + ch];
+        }
+      for (int t = 0; t < T; ++t)
+        for (int g = 0; g < kD / G; ++g) {
+          vs[((size_t)h * p.Tcap + t) * (kD / G) + g] = v_scale[((size_t)h * T + t) * (kD / G) + g];
+          vz[((size_t)h * p.Tcap + t) * (kD / G) + g] = v_zero[((size_t)h * T + t) * (kD / G) + g];
+        }
+    }
+    good = good && hipMemcpy(lc.ks, ks.data(), ks.size() * 4, hipMemcpyHostToDevice) == hipSuccess &&
+           hipMemcpy(lc.kz, kz.data(), kz.size() * 4, hipMemcpyHostToDevice) == hipSuccess &&
+           hipMemcpy(lc.vs, vs.data(), vs.size() * 4, hipMemcpyHostToDevice) == hipSuccess &&
+           hipMemcpy(lc.vz, vz.data(), vz.size() * 4, hipMemcpyHostToDevice) == hipSuccess;
+  }
+  if (T > 0)
+    good = good && hipMemcpy(lc.tok_frame, token_frame, (size_t)T * 4, hipMemcpyHostToDevice) == hipSuccess &&
+           hipMemcpy(lc.tok_index, token_index, (size_t)T * 4, hipMemcpyHostToDevice) == hipSuccess;
+  if (!good) return hip_fail(ctx);
+  L.T = T;
+  L.frames = frames_seen;
+  L.last_P = 0;
+  L.last_keep = 0;
+  return XSV_OK;
+}
+
+int xsv_last_selection(xsv_ctx* ctx, int layer, int32_t* n_scores, float* scores, int32_t* n_keep, int32_t* keep) {
+  int rc = check_layer(ctx, layer);
+  if (rc != XSV_OK) return rc;
+  const LayerState& L = ctx->layers[layer];
+  if (n_scores) *n_scores = L.last_P;
+  if (n_keep) *n_keep = L.last_keep;
+  bool good = true;
+  if (scores && L.last_P > 0)
+    good = hipMemcpyAsync(scores, ctx->ws.scores + (size_t)layer * ctx->ws.scores_stride, (size_t)L.last_P * 4,
+                          hipMemcpyDeviceToHost, ctx->stream) == hipSuccess;
+  if (keep && L.last_keep > 0 && good)
+    good = hipMemcpyAsync(keep, ctx->ws.keep + (size_t)layer * ctx->ws.scores_stride, (size_t)L.last_keep * 4,
+                          hipMemcpyDeviceToHost, ctx->stream) == hipSuccess;
+  if (!good || hipStreamSynchronize(ctx->stream) != hipSuccess) return hip_fail(ctx);
+  return XSV_OK;
+}
+
+// ---- stateless entry points: a throw-away one-layer context around the same kernels ----------------
+
+static int quantize_plain(void* hip_stream, const void* x, int H, int T, int d, int bits, int G, void* codes, float* scale,
+                          float* zero, bool keys) {
+  if (!x || !codes || !scale || !zero || H < 1 || T < 1) return XSV_ERR_ARG;
+  if (d != kD) return XSV_ERR_UNSUPPORTED;
+  if (bits != 2 && bits != 4) return XSV_ERR_ARG;
+  if (G != 32 && G != 64) return XSV_ERR_UNSUPPORTED;
+  xsv_config c{};
+  c.n_layers = 1; c.n_heads = H; c.head_dim = d; c.tokens_per_frame = T; c.n_special = 0; c.budget = 0;
+  c.kv_bits = bits; c.group_size = G; c.pool_size = 1; c.max_frames = 1;
+  xsv_ctx* ctx = nullptr;
+  int rc = xsv_create(&c, hip_stream, &ctx);
+  if (rc != XSV_OK) return rc;
+  // the whole tensor is "the current frame" of an empty cache: keep everything, quantize
+  const xsv_tensor t{x, (int64_t)T * d, d};
+  ctx->layers[0].phase = kAttended;
+  rc = do_score_prune(ctx, 0, 1, nullptr);
+  if (rc == XSV_OK) rc = do_quantize(ctx, 0, 1, &t, &t);
+  if (rc == XSV_OK) {
+    UnpackArgs u{};
+    u.pool = ctx->pool; u.buf = ctx->layers[0].buf; u.layer = 0; u.T = T;
+    if (keys) { u.k_codes = static_cast<uint8_t*>(codes); u.k_scale = scale; u.k_zero = zero; }
+    else { u.v_codes = static_cast<uint8_t*>(codes); u.v_scale = scale; u.v_zero = zero; }
+    if (launch_unpack(u, ctx->stream) != hipSuccess) rc = XSV_ERR_HIP;
+  }
+  xsv_destroy(ctx);  // synchronizes
+  return rc;
+}
+
+int xsv_quantize_k(void* hip_stream, const void* k_bf16, int H, int T, int d, int bits, int G, void* codes_u8,
+                   float* scale, float* zero) {
+  return quantize_plain(hip_stream, k_bf16, H, T, d, bits, G, codes_u8, scale, zero, true);
+}
+
+int xsv_quantize_v(void* hip_stream, const void* v_bf16, int H, int T, int d, int bits, int G, void* codes_u8,
+                   float* scale, float* zero) {
+  return quantize_plain(hip_stream, v_bf16, H, T, d, bits, G, codes_u8, scale, zero, false);
+}
+
+int xsv_score(void* hip_stream, xsv_tensor q, const void* k_mid_bf16, int H, int n, int n_s, int P, int d, int g,
+              float* scores) {
+  if (!tensor_ok(q) || !k_mid_bf16 || !scores || H < 1 || n < 1 || n_s < 0 || n_s > n || P < 1 || g < 1) return XSV_ERR_ARG;
+  if (d != kD) return XSV_ERR_UNSUPPORTED;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  Temp tmp;
+  ScoreArgs s{};
+  s.pool.H = H; s.pool.L = 1; s.pool.bits = 16; s.pool.G = 64; s.pool.Tcap = round_up(P, kTile);
+  s.b.n_layers = 1; s.b.layer0 = 0;
+  s.b.q[0] = static_cast<const uint16_t*>(q.ptr);
+  s.b.q_sh = q.stride_head; s.b.q_st = q.stride_token;
+  s.ws.qpart_rows = ((n + 127) / 128) * H;
+  s.ws.qpart = tmp.get<float>((size_t)s.ws.qpart_rows * kD);
+  if (!s.ws.qpart) return XSV_ERR_OOM;
+  s.ws.scores = scores;
+  s.ws.scores_stride = P;
+  s.Tc = P; s.n = n; s.n_special = n_s; s.pool_size = g; s.T_first = 0; s.P = P;
+  s.k_plain = static_cast<const uint16_t*>(k_mid_bf16);
+  if (launch_pool_query(s, stream) != hipSuccess || launch_score(s, stream) != hipSuccess) return XSV_ERR_HIP;
+  return hipStreamSynchronize(stream) == hipSuccess ? XSV_OK : XSV_ERR_HIP;
+}
+
+int xsv_topk_keep(void* hip_stream, const float* scores, int P, int k, int T_first, int T_cur, int32_t* keep) {
+  if (!keep || P < 0 || k < 0 || k > P || T_first < 0 || T_cur < 0 || (P > 0 && !scores)) return XSV_ERR_ARG;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  hipError_t e;
+  if (k == 0 || k == P) {
+    e = launch_fill_keep(keep, 0, 1, T_first, P, T_cur, k == P, stream);
+  } else {
+    SelectArgs s{};
+    s.scores = scores; s.keep = keep; s.n_layers = 1; s.P = P; s.k = k; s.T_first = T_first; s.T_cur = T_cur;
+    e = launch_select(s, stream);
+  }
+  if (e != hipSuccess) return XSV_ERR_HIP;
+  return hipStreamSynchronize(stream) == hipSuccess ? XSV_OK : XSV_ERR_HIP;
+}
+
+}  // extern "C"

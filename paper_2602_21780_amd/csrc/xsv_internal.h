@@ -1,0 +1,154 @@
+// Internal layouts shared by the host API and the HIP kernels of libxsv (not part of the ABI).
+//
+// Packed cache of one layer (per head), private to the library:
+//   keys    kc  [Tcap][64*bits/8 B]     one row per token, channel c at bit c*bits (little endian)
+//           ks, kz [Tcap/G][64] fp32    scale / zero point per (group of G tokens, channel)
+//   values  vc  [Tcap/64][64][64*bits/8 B]  blocks of 64 tokens, TRANSPOSED: one row per channel,
+//                                       token j of the block at bit j*bits — so that 8 (16) tokens
+//                                       of one channel are one dword, the unit the PV MFMA consumes
+//           vs, vz [Tcap][64/G] fp32    scale / zero point per (token, group of G channels)
+//   bits == 16: kc rows are 64 bf16, vc rows are 64 bf16 (still transposed in 64-token blocks).
+//   token ids   tok_frame, tok_index [Tcap] (per layer, shared by the heads)
+// Every layer has two such buffers; a step reads one and writes the other.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace xsv {
+
+constexpr int kD = 64;         // head_dim
+constexpr int kTile = 64;      // tokens per value block and per attention key tile
+constexpr int kMaxBatch = 32;  // layers per batched launch
+
+struct CachePool {
+  uint8_t* kc;
+  float* ks;
+  float* kz;
+  uint8_t* vc;
+  float* vs;
+  float* vz;
+  int32_t* tok_frame;
+  int32_t* tok_index;
+  int L, H, Tcap, bits, G;
+
+  // slab = one (buffer, layer); sizes in elements of the respective array
+  __host__ __device__ size_t code_row_bytes() const { return (size_t)kD * bits / 8; }
+  __host__ __device__ size_t code_slab() const { return (size_t)H * Tcap * code_row_bytes(); }
+  __host__ __device__ size_t kparam_slab() const { return (size_t)H * (Tcap / G) * kD; }
+  __host__ __device__ size_t vparam_slab() const { return (size_t)H * Tcap * (kD / G); }
+  __host__ __device__ size_t tok_slab() const { return (size_t)Tcap; }
+  __host__ __device__ size_t slab_index(int buf, int layer) const { return (size_t)buf * L + layer; }
+};
+
+// One layer's view of the pool (device pointers of one buffer), head 0.
+struct LayerCache {
+  uint8_t* kc;
+  float* ks;
+  float* kz;
+  uint8_t* vc;
+  float* vs;
+  float* vz;
+  int32_t* tok_frame;
+  int32_t* tok_index;
+};
+
+__host__ __device__ inline LayerCache layer_cache(const CachePool& p, int buf, int layer) {
+  const size_t i = p.slab_index(buf, layer);
+  LayerCache c;
+  c.kc = p.kc + i * p.code_slab();
+  c.vc = p.vc + i * p.code_slab();
+  c.ks = p.ks ? p.ks + i * p.kparam_slab() : nullptr;
+  c.kz = p.kz ? p.kz + i * p.kparam_slab() : nullptr;
+  c.vs = p.vs ? p.vs + i * p.vparam_slab() : nullptr;
+  c.vz = p.vz ? p.vz + i * p.vparam_slab() : nullptr;
+  c.tok_frame = p.tok_frame + i * p.tok_slab();
+  c.tok_index = p.tok_index + i * p.tok_slab();
+  return c;
+}
+
+// The layers one launch works on, and their frame tensors.
+struct Batch {
+  int n_layers;     // layers in this launch
+  int layer0;       // pool index of the first
+  uint32_t bufsel;  // bit i: buffer that currently holds layer (layer0+i)'s cache
+  const uint16_t* q[kMaxBatch];
+  const uint16_t* k[kMaxBatch];
+  const uint16_t* v[kMaxBatch];
+  uint16_t* out[kMaxBatch];
+  int64_t q_sh, q_st, k_sh, k_st, v_sh, v_st;  // strides in elements
+
+  __host__ __device__ int src_buf(int i) const { return (bufsel >> i) & 1; }
+};
+
+// Per-layer workspaces (device), indexed by pool layer.
+struct Workspace {
+  float* scores;      // [L][Tcap + n]      importance of the middle tokens
+  int32_t* keep;      // [L][Tcap + n]      keep list
+  float* qpart;       // [L][qpart_rows][64] partial weighted query sums
+  float* attn_o;      // [splits][batch layers][H][n][64] unnormalized partial outputs
+  float* attn_ml;     // [splits][batch layers][H][n][2]  running max (log2 domain), row sum
+  int scores_stride;  // Tcap + n
+  int qpart_rows;
+};
+
+// ---- launchers (defined in the .hip files; every one only enqueues on `stream`) -----------------
+
+struct AttendArgs {
+  CachePool pool;
+  Batch b;
+  Workspace ws;
+  int Tc, n, n_splits;
+  float qscale;  // softmax scale * log2(e)
+};
+hipError_t launch_attend(const AttendArgs& a, hipStream_t stream);
+
+struct ScoreArgs {
+  CachePool pool;
+  Batch b;
+  Workspace ws;
+  int Tc, n, n_special, pool_size;
+  int T_first, P;  // middle = cache positions [T_first, T_first + P)
+  // stateless form: keys come from a plain bf16 tensor [H][P][64] instead of the pool
+  const uint16_t* k_plain;
+};
+hipError_t launch_pool_query(const ScoreArgs& a, hipStream_t stream);
+hipError_t launch_score(const ScoreArgs& a, hipStream_t stream);
+
+struct SelectArgs {
+  const float* scores;  // [n_layers][scores_stride]
+  int32_t* keep;        // [n_layers][keep_stride]
+  int scores_stride, keep_stride;
+  int n_layers;
+  int P, k, T_first, T_cur;
+};
+hipError_t launch_select(const SelectArgs& a, hipStream_t stream);
+// keep = 0..T-1 (nothing pruned) or first ∪ current (k == 0)
+hipError_t launch_fill_keep(int32_t* keep, int keep_stride, int n_layers, int T_first, int P, int T_cur,
+                            bool keep_middle, hipStream_t stream);
+
+struct RequantArgs {
+  CachePool pool;
+  Batch b;
+  Workspace ws;
+  int Tc, n, Tn;  // old cache length, frame tokens, new cache length (= keep length)
+  int frame_id;
+};
+hipError_t launch_requant(const RequantArgs& a, hipStream_t stream);
+
+// Canonical (one code per byte, untransposed) copies of one layer buffer → device arrays.
+struct UnpackArgs {
+  CachePool pool;
+  int buf, layer, T;
+  uint8_t* k_codes;  // [H][T][64] or null
+  float* k_scale;    // [H][ceil(T/G)][64]
+  float* k_zero;
+  uint8_t* v_codes;
+  float* v_scale;  // [H][T][64/G]
+  float* v_zero;
+  uint16_t* k_bf16;  // [H][T][64] dequantized view / stored rows
+  uint16_t* v_bf16;
+};
+hipError_t launch_unpack(const UnpackArgs& a, hipStream_t stream);
+
+}  // namespace xsv

@@ -1,0 +1,62 @@
+"""Host-only checks of the C-ABI library: it loads, exports every declared symbol, and rejects bad
+arguments before touching a GPU.  CPU only."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2602_21780_amd import xsv
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(xsv.LIB_PATH):
+        from paper_2602_21780_amd.build import build
+        build()
+    return xsv.lib()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "xsv.h")).read()
+    declared = set(re.findall(r"\b(xsv_[a-z_]+)\s*\(", header))
+    assert declared == set(xsv.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_strerror(lib):
+    assert xsv.strerror(0) == "ok"
+    for code in (-1, -2, -3, -4, -5, -99):
+        assert xsv.strerror(code)
+
+
+def test_create_rejects_bad_configurations_on_the_host(lib):
+    good = dict(n_layers=1, n_heads=2, head_dim=64, tokens_per_frame=64, n_special=5, budget=256, kv_bits=4,
+                group_size=32, pool_size=16, softmax_scale=0.0, max_frames=0)
+    def create(**kw):
+        cfg = xsv.xsv_config(**{**good, **kw})
+        h = C.c_void_p()
+        return lib.xsv_create(C.byref(cfg), None, C.byref(h))
+    assert create(n_layers=0) == xsv.XSV_ERR_ARG
+    assert create(n_heads=0) == xsv.XSV_ERR_ARG
+    assert create(kv_bits=3) == xsv.XSV_ERR_ARG
+    assert create(budget=-1) == xsv.XSV_ERR_ARG
+    assert create(n_special=65) == xsv.XSV_ERR_ARG
+    assert create(pool_size=0) == xsv.XSV_ERR_ARG
+    assert create(budget=0, max_frames=0) == xsv.XSV_ERR_ARG
+    assert create(head_dim=128) == xsv.XSV_ERR_UNSUPPORTED
+    assert create(group_size=16) == xsv.XSV_ERR_UNSUPPORTED
+    assert lib.xsv_create(None, None, None) == xsv.XSV_ERR_ARG
+
+
+def test_null_context_is_rejected(lib):
+    t = xsv.xsv_tensor(None, 0, 0)
+    assert lib.xsv_step(None, 0, t, t, t, None) == xsv.XSV_ERR_ARG
+    assert lib.xsv_reset(None) == xsv.XSV_ERR_ARG
+    assert lib.xsv_destroy(None) == xsv.XSV_OK
+    assert lib.xsv_cache_len(None, 0, None) == xsv.XSV_ERR_ARG
+    assert lib.xsv_quantize_k(None, None, 1, 1, 64, 4, 64, None, None, None) == xsv.XSV_ERR_ARG
+    assert lib.xsv_topk_keep(None, None, 4, 5, 0, 0, None) == xsv.XSV_ERR_ARG

@@ -1,0 +1,84 @@
+"""GPU parity of the stateless entry points against the oracle (through the C ABI)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2602_21780_amd import xsv
+from paper_2602_21780_amd.inputs import to_u16
+from oracle import ref
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def randn_bf16(shape, seed, scale=1.0, outliers=()):
+    g = torch.Generator().manual_seed(seed)
+    x = torch.randn(shape, generator=g) * scale
+    for c in outliers:
+        x[..., c] *= 8.0
+    return x.to(torch.bfloat16).to(DEV)
+
+
+@pytest.mark.parametrize("bits,G", [(4, 64), (4, 32), (2, 64), (2, 32)])
+@pytest.mark.parametrize("H,T", [(2, 64), (3, 150), (1, 1), (16, 1374)])
+def test_quantize_k_and_v_bit_exact(bits, G, H, T):
+    print(f"quantize bits={bits} G={G} H={H} T={T}", flush=True)
+    x = randn_bf16((H, T, 64), 17 * T + bits + G, 1.5, outliers=(3, 40))
+    x16 = to_u16(x)
+    for fn_gpu, fn_ref in ((xsv.quantize_k, ref.quantize_k), (xsv.quantize_v, ref.quantize_v)):
+        codes, scale, zero = fn_gpu(x, bits, G)
+        rc, rs, rz = fn_ref(x16, bits, G)
+        assert np.array_equal(codes.cpu().numpy(), rc)
+        assert np.array_equal(scale.cpu().numpy(), rs)
+        assert np.array_equal(zero.cpu().numpy(), rz)
+
+
+def test_quantize_degenerate_groups():
+    # constant groups (s = 1 fallback), groups away from zero (zero point outside the code range),
+    # exact half-way values (ties to even)
+    x = torch.zeros((1, 64, 64))
+    x[0, :, 0] = 3.0
+    x[0, :, 1] = torch.linspace(5, 6, 64)
+    x[0, :, 2] = torch.arange(64) * 0.5
+    x[0, 5, :] = 7.0
+    xb = x.to(torch.bfloat16).to(DEV)
+    for fn_gpu, fn_ref in ((xsv.quantize_k, ref.quantize_k), (xsv.quantize_v, ref.quantize_v)):
+        for bits in (2, 4):
+            codes, scale, zero = fn_gpu(xb, bits, 64)
+            rc, rs, rz = fn_ref(to_u16(xb), bits, 64)
+            assert np.array_equal(codes.cpu().numpy(), rc)
+            assert np.array_equal(scale.cpu().numpy(), rs) and np.array_equal(zero.cpu().numpy(), rz)
+
+
+@pytest.mark.parametrize("H,n,n_s,P,g", [(2, 64, 5, 192, 16), (16, 1374, 5, 2722, 16), (3, 37, 5, 70, 4), (1, 21, 0, 1, 1)])
+def test_score_matches_oracle(H, n, n_s, P, g):
+    print(f"score H={H} n={n} P={P}", flush=True)
+    q = randn_bf16((H, n, 64), n + P)
+    k = randn_bf16((H, P, 64), n + P + 1, outliers=(7, 21, 33))
+    s = xsv.score(q, k, n_s, g).cpu().numpy()
+    expect, _ = ref.score(to_u16(q), to_u16(k), n_s, g)
+    # fp32 sums in a different order: a few ulp of the largest score
+    err = float(np.max(np.abs(s - expect)))
+    assert err <= 1e-6 * (1.0 + float(np.abs(expect).max())), err
+    # strided query tensor (a view into a larger buffer) gives the same bits
+    big = torch.zeros((H, n, 128), dtype=torch.bfloat16, device=DEV)
+    big[:, :, :64] = q
+    s2 = xsv.score(big[:, :, :64], k, n_s, g).cpu().numpy()
+    assert np.array_equal(s, s2)
+
+
+@pytest.mark.parametrize("P,k", [(1, 1), (50, 0), (50, 50), (257, 100), (2722, 1348), (7151, 6110), (40000, 12345)])
+def test_topk_keep_bit_exact_with_ties(P, k):
+    print(f"topk P={P} k={k}", flush=True)
+    g = torch.Generator().manual_seed(P)
+    tied = (torch.randint(0, 50, (P,), generator=g).float() / 8 - 3).to(DEV)        # many exact ties, both signs
+    smooth = torch.randn(P, generator=g).to(DEV)
+    for scores in (tied, smooth):
+        keep = xsv.topk_keep(scores, k, 7, 5).cpu().numpy()
+        assert np.array_equal(keep, ref.select(scores.cpu().numpy(), k, 7, 5))
+
+
+def test_topk_keep_all_equal_scores_take_smallest_positions():
+    scores = torch.zeros(1000, device=DEV)
+    keep = xsv.topk_keep(scores, 10, 0, 0).cpu().numpy()
+    assert keep.tolist() == list(range(10))

@@ -1,0 +1,158 @@
+"""GPU parity of the streaming step against the oracle, frame by frame, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2602_21780_amd import xsv
+from paper_2602_21780_amd.inputs import CONFIGS, FrameSource, to_u16
+from oracle import ref
+import parity
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def run_stream(spec, frames, rows=None, splits=0, **over):
+    ctx, st = parity.make_pair(spec, **over)
+    if splits:
+        ctx.set_attend_splits(splits, splits)
+    src = FrameSource(spec, DEV)
+    worst = (0.0, 0.0)
+    ties = 0
+    for f in range(frames):
+        q, k, v = src.frame(f)
+        for l in range(spec.n_layers):
+            print(f"  {spec.name} frame {f} layer {l} T={ctx.cache_len(l)}", flush=True)
+            (ma, rr), t = parity.step_and_compare(ctx, st, spec, l, l, q[l], k[l], v[l], rows=rows,
+                                                  budget=over.get("budget"))
+            worst = (max(worst[0], ma), max(worst[1], rr))
+            ties += t
+    print(f"  worst max_abs={worst[0]:.3e} rel_rms={worst[1]:.3e} ties={ties}", flush=True)
+    ctx.destroy()
+    return worst, ties
+
+
+def test_tiny_config_full_stream():
+    """cfg 0: every frame, every row, every exported byte."""
+    run_stream(CONFIGS[0], CONFIGS[0].frames)
+
+
+@pytest.mark.parametrize("splits", [1, 2, 5])
+def test_tiny_config_key_range_splits(splits):
+    run_stream(CONFIGS[0], 6, splits=splits)
+
+
+@pytest.mark.parametrize("bits,G", [(4, 64), (2, 64), (2, 32), (16, 64)])
+def test_mid_size_streams_all_code_widths(bits, G):
+    # several query tiles and key tiles, ragged everywhere: n = 5 + 195, budget not a multiple of 64
+    spec = CONFIGS[0].with_(name=f"mid-b{bits}-g{G}", n_heads=3, tokens_per_frame=200, budget=700, kv_bits=bits,
+                            group_size=G, n_layers=2, seed=11)
+    run_stream(spec, 6)
+
+
+def test_budget_below_two_frames_keeps_first_and_current():
+    spec = CONFIGS[0].with_(name="k0", budget=100)
+    run_stream(spec, 4)
+
+
+def test_unbounded_bf16_cache_matches_brute_force_attention():
+    """No pruning, no quantization: the streamed GPU outputs are plain frame-causal attention."""
+    spec = CONFIGS[0].with_(name="plain", budget=0, kv_bits=16)
+    run_stream(spec, 5)
+
+
+def test_batched_all_layers_equals_per_layer_steps():
+    spec = CONFIGS[0].with_(name="batched", n_layers=3, n_heads=4, tokens_per_frame=150, budget=400, group_size=64, seed=5)
+    ctx_a = xsv.Context.from_spec(spec)
+    ctx_b = xsv.Context.from_spec(spec)
+    src = FrameSource(spec, DEV)
+    for f in range(5):
+        q, k, v = src.frame(f)
+        out_a = ctx_a.step_all_layers(q, k, v)
+        out_b = torch.stack([ctx_b.step(l, q[l], k[l], v[l]) for l in range(spec.n_layers)])
+        torch.cuda.synchronize()
+        assert torch.equal(out_a, out_b)
+        for l in range(spec.n_layers):
+            da, db = ctx_a.cache_export(l), ctx_b.cache_export(l)
+            parity.compare_cache(da, db, True)
+    ctx_a.destroy()
+    ctx_b.destroy()
+
+
+def test_same_inputs_twice_give_identical_bytes():
+    spec = CONFIGS[0].with_(name="determinism", n_heads=4, tokens_per_frame=150, budget=400, group_size=64)
+    dumps = []
+    for _ in range(2):
+        ctx = xsv.Context.from_spec(spec)
+        ctx.set_attend_splits(3, 0)
+        src = FrameSource(spec, DEV)
+        outs = []
+        for f in range(5):
+            q, k, v = src.frame(f)
+            outs.append(ctx.step(0, q[0], k[0], v[0]).clone())
+        torch.cuda.synchronize()
+        dumps.append((torch.stack(outs).cpu(), ctx.cache_export(0), ctx.last_selection(0)))
+        ctx.destroy()
+    assert torch.equal(dumps[0][0], dumps[1][0])
+    parity.compare_cache(dumps[0][1], dumps[1][1], True)
+    assert np.array_equal(dumps[0][2][0], dumps[1][2][0]) and np.array_equal(dumps[0][2][1], dumps[1][2][1])
+
+
+def test_import_of_oracle_cache_then_attend():
+    """dequant_attend alone, on a cache produced by the oracle (isolates it from the GPU quantizer)."""
+    spec = CONFIGS[0].with_(name="import", n_heads=3, tokens_per_frame=100, budget=300, group_size=64)
+    ctx, st = parity.make_pair(spec)
+    src = FrameSource(spec, DEV)
+    for f in range(4):
+        q, k, v = src.frame(f)
+        st.step(0, to_u16(q[0]), to_u16(k[0]), to_u16(v[0]), attend=False)
+    c = st.export(0)
+    ctx.cache_import(0, c, frames_seen=4)
+    parity.compare_cache(ctx.cache_export(0), c, True)
+    q, k, v = src.frame(4)
+    out = ctx.dequant_attend(0, q[0], k[0], v[0])
+    expect, _ = st.step(0, to_u16(q[0]), to_u16(k[0]), to_u16(v[0]))
+    parity.check_attention(to_u16(out), expect)
+    ctx.destroy()
+
+
+def test_call_order_is_enforced():
+    spec = CONFIGS[0]
+    ctx = xsv.Context.from_spec(spec)
+    q, k, v = (t[0] for t in FrameSource(spec, DEV).frame(0))
+    with pytest.raises(xsv.XsvError) as e:
+        ctx.quantize(0, k, v)
+    assert e.value.code == xsv.XSV_ERR_STATE
+    ctx.dequant_attend(0, q, k, v)
+    with pytest.raises(xsv.XsvError):
+        ctx.dequant_attend(0, q, k, v)
+    ctx.score_prune(0, q)
+    ctx.quantize(0, k, v)
+    assert ctx.cache_len(0) == spec.tokens_per_frame
+    with pytest.raises(xsv.XsvError):
+        ctx.step(1, q, k, v)  # no such layer
+    ctx.reset()
+    assert ctx.cache_len(0) == 0
+    ctx.destroy()
+
+
+def test_one_layer_config_full_size_sampled_rows():
+    """cfg 1 at its real shape (16 heads, 1374 tokens, budget 2048 < first + current, so k = 0):
+    cache bytes compared in full, attention on sampled query rows incl. the ragged last tile."""
+    spec = CONFIGS[1]
+    rows = np.array([0, 4, 5, 31, 32, 700, 1343, 1344, 1372, 1373], np.int32)
+    run_stream(spec, 4, rows=rows)
+
+
+def test_24_layer_config_shape_two_layers_sampled_rows():
+    """cfg 2 shape (budget 4096, top-k of 1348 from 2722 once saturated) on two of its layers."""
+    spec = CONFIGS[2].with_(n_layers=2)
+    rows = np.array([0, 3, 64, 777, 1311, 1373], np.int32)
+    run_stream(spec, 6, rows=rows)
+
+
+def test_2bit_config_shape_sampled_rows():
+    """cfg 4 shape (1041 tokens, 2-bit, budget 8192) on one layer until the first prune."""
+    spec = CONFIGS[4].with_(n_layers=1)
+    rows = np.array([0, 5, 1000, 1040], np.int32)
+    run_stream(spec, 9, rows=rows)
