@@ -100,7 +100,10 @@ int xsv_score_prune(xsv_ctx* ctx, int layer, xsv_tensor q);
  * stored as bf16 unchanged.  Swaps the layer's cache buffers; cache length becomes the keep length. */
 int xsv_quantize(xsv_ctx* ctx, int layer, xsv_tensor k_new, xsv_tensor v_new);
 
-/* The three calls above, in order, for one layer. */
+/* The three calls above for one layer.  Attention runs on the context's stream while score, select
+ * and re-quantization run concurrently on a stream owned by the context (they read the same inputs
+ * and write the layer's other cache buffer); when the call returns, the context's stream is ordered
+ * after both, so the usual "valid until the stream has passed the call" rule holds. */
 int xsv_step(xsv_ctx* ctx, int layer, xsv_tensor q, xsv_tensor k_new, xsv_tensor v_new, void* out);
 
 /* One frame through ALL layers with layer-batched launches (arrays of n_layers entries; every
@@ -113,6 +116,12 @@ int xsv_step_all_layers(xsv_ctx* ctx, const xsv_tensor* q, const xsv_tensor* k_n
 /* Tuning: number of key ranges one (head, query block) is split into by xsv_dequant_attend
  * (partial results are merged by a second kernel).  0 = choose from the launch size.  1..16. */
 int xsv_set_attend_splits(xsv_ctx* ctx, int per_layer_calls, int batched_calls);
+/* Tuning: 0 = xsv_step / xsv_step_all_layers run everything on the context's stream, in order;
+ * 1 (default) = the score/select/re-quantize chain overlaps the attention kernel. */
+int xsv_set_overlap(xsv_ctx* ctx, int enabled);
+/* Tuning: workgroup shape of the attention kernel.  0 (default) = 4 waves x 64 query rows,
+ * 1 = 4 waves x 32 rows, 2 = 8 waves x 32 rows.  Results are the same to rounding. */
+int xsv_set_attend_variant(xsv_ctx* ctx, int variant);
 
 /* ---- introspection, synchronous, HOST buffers, canonical unpacked layout ------------------------ */
 

@@ -2,17 +2,20 @@
 // (paper Sec. 3.1 temporal attention, Sec. 3.3 dequantization at attention time) for gfx950.
 //
 // Work decomposition
-//   workgroup = NW waves; each wave owns 32 query rows of one head and keeps, per lane, the
-//   transposed tiles  S^T = K Q^T  (64 tokens x 32 queries)  and  O^T = V^T P^T  (64 channels x 32
-//   queries) in MFMA 32x32x16 bf16 accumulators.  In this orientation one lane holds 32 logits of
-//   ONE query, so the online-softmax row reductions are in-lane plus one exchange with lane^32, and
-//   the exponentiated tile is already laid out as the B operand of the PV product — provided the
-//   key rows of the first product are read in a permuted order (tau below), which costs nothing.
-//   The workgroup walks the key axis in tiles of 64 tokens.  All waves cooperatively dequantize a
-//   tile ONCE into LDS as bf16 (K row-major [token][channel], V transposed [channel][token], the
-//   layout the packed cache already has), so the unpack/convert cost is shared by NW*32 queries.
-//   LDS is double buffered; the next tile's packed codes and group parameters are fetched into
-//   registers before the current tile's MFMAs are issued.
+//   workgroup = NW waves; each wave owns QB blocks of 32 query rows of one head and keeps, per
+//   lane, the transposed tiles  S^T = K Q^T  (32 tokens x 32 queries per block)  and
+//   O^T = V^T P^T  (64 channels x 32 queries per block) in MFMA 32x32x16 bf16 accumulators.  In
+//   this orientation one lane holds the logits of ONE query, so the online-softmax row reductions
+//   are in-lane plus one exchange with lane^32, and the exponentiated tile is already laid out as
+//   the B operand of the PV product — provided the key rows of the first product are read in a
+//   permuted order (tau below), which costs nothing.  Every K / V fragment read from LDS feeds QB
+//   MFMAs.
+//   The workgroup walks the key axis in tiles of 64 tokens (two half-steps of 32).  All waves
+//   cooperatively dequantize a tile ONCE into LDS as bf16 (K row-major [token][channel], V
+//   transposed [channel][token], the layout the packed cache already has), so the unpack/convert
+//   cost is shared by NW*QB*32 queries (half of the threads stage K, the other half V, with the
+//   same code on mirrored layouts).  LDS is double buffered; the next tile's packed codes and
+//   group parameters are fetched into registers before the current tile's MFMAs are issued.
 //   blockIdx is remapped so that all query blocks of one (layer, head, key range) land on the same
 //   XCD and share its L2.  With n_splits > 1 each key range writes unnormalized partials that
 //   combine_kernel merges.
@@ -21,17 +24,18 @@
 namespace xsv {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr int kLdsStride = 72;  // bf16 elements per LDS row: 64 + 8 pad (144 B, keeps 16 B alignment)
 constexpr float kNegBig = -1.0e30f;
+constexpr float kLazyLog2 = 8.0f;  // headroom of the lazily updated softmax reference, in powers of two
 
-__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+typedef __attribute__((ext_vector_type(2))) float f32x2;
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
-  __bf16 x = (__bf16)a, y = (__bf16)b;  // round to nearest even (v_cvt_pk_bf16_f32)
-  return (uint32_t)__builtin_bit_cast(unsigned short, x) | ((uint32_t)__builtin_bit_cast(unsigned short, y) << 16);
+  const f32x2 v = {a, b};  // one v_cvt_pk_bf16_f32: round to nearest even, a in the low half
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
 // Row of the K tile that MFMA row i of S^T reads, so that accumulator register r of the lane
@@ -41,143 +45,170 @@ __device__ __forceinline__ int tau(int i) {
   return 16 * (a >> 1) + 8 * ((i >> 2) & 1) + 4 * (a & 1) + (i & 3);
 }
 
+// code e (0 .. 32/BITS-1) of a packed dword as float; the masks are shared between neighbours
+template <int BITS>
+__device__ __forceinline__ void unpack_codes(uint32_t w, float* out) {
+  if constexpr (BITS == 4) {
+    const uint32_t t0 = w & 0x0f0f0f0fu, t1 = (w >> 4) & 0x0f0f0f0fu;
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+      out[2 * b] = (float)((t0 >> (8 * b)) & 0xffu);  // v_cvt_f32_ubyte<b>
+      out[2 * b + 1] = (float)((t1 >> (8 * b)) & 0xffu);
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t t = (w >> (2 * i)) & 0x03030303u;
+#pragma unroll
+      for (int b = 0; b < 4; ++b) out[4 * b + i] = (float)((t >> (8 * b)) & 0xffu);
+    }
+  }
+}
+
 // ---- staging of one key tile -------------------------------------------------------------------
-// Raw (still packed) data of the items one thread stages, fetched ahead of use.
-template <int BITS, int G, int NT>
-struct Staged {
-  static constexpr int kDw = (BITS == 16) ? 4 : 1;                    // dwords per item
-  static constexpr int kPer = (BITS == 16) ? 8 : 32 / BITS;           // elements per item
-  static constexpr int kItems = kTile * kD / kPer;                    // items per tile (K, same for V)
-  static constexpr int kRowItems = kD / kPer;                         // items per K row / V block row
-  static constexpr int kIter = (kItems + NT - 1) / NT;
-  uint32_t k[kIter][4];
-  uint32_t v[kIter][4];
-  float ks[kIter][kPer > 8 ? 16 : 8], kz[kIter][kPer > 8 ? 16 : 8];
-  float vs[kIter][kPer > 8 ? 16 : 8], vz[kIter][kPer > 8 ? 16 : 8];
+// A tile is 64 tokens x 64 channels of K and of V.  It is cut into "items" of one dword of codes
+// (8 or 16 elements; bf16 tiles: 16 bytes = 8 elements).  The first half of the workgroup's threads
+// stages K, the second half V; both run the SAME code on different pointers, because the packed
+// layouts mirror each other:  K item i = (token i / RI, channel run i % RI) with per-channel
+// parameters,  V item i = (channel i / RI, token run i % RI) with per-token parameters, and the
+// LDS tile of either is [row = i / RI][column run].  A thread stages items u, u + NH, .. (u = its
+// index within its half, NH threads per half); NH is a multiple of RI, so all its items share the
+// column run and (within a group) the parameters.
+template <int BITS, int G, int NH>
+struct Stage {
+  static constexpr bool kQuant = BITS != 16;
+  static constexpr int kPer = kQuant ? 32 / BITS : 8;  // elements per item
+  static constexpr int kRI = kD / kPer;                 // items per row
+  static constexpr int kItems = kTile * kRI;            // per tile and role
+  static constexpr int kIter = kItems / NH;             // items per thread
+  static constexpr int kRowStep = NH / kRI;             // rows between a thread's consecutive items
+  // parameter sets per thread: with G = 32 the rows < 32 and >= 32 of a tile are different groups
+  static constexpr int kSets = (G >= 64 || kIter == 1) ? 1 : 2;
+  static_assert(kItems % NH == 0 && NH % kRI == 0, "thread count must tile the items");
+  static_assert(kSets == 1 || (kIter % 2 == 0 && kRowStep * (kIter / 2) == 32), "two groups need an even split");
+
+  uint32_t code[kQuant ? kIter : 1];
+  float ps[kQuant ? kSets : 1][kPer], pz[kQuant ? kSets : 1][kPer];
+  uint4 row[kQuant ? 1 : kIter];  // bf16 cache
 };
 
-// A tile either comes from the packed cache (CACHE = true) or from the frame's own bf16 K/V.
-template <int BITS, int G, int NT>
-__device__ __forceinline__ void fetch_cache_tile(Staged<BITS, G, NT>& st, const CachePool& pool,
-                                                 const LayerCache& lc, int h, int tile, int tid) {
-  using S = Staged<BITS, G, NT>;
+struct RolePtrs {      // what distinguishes the K half from the V half
+  const uint32_t* codes;  // packed tile base of (layer, head): row-major [Tcap rows][row dwords]
+  const float* ps;        // parameter arrays of (layer, head)
+  const float* pz;
+  uint16_t* lds[2];       // the two LDS tiles of this role
+  bool is_v;
+};
+
+template <int BITS, int G, int NH>
+__device__ __forceinline__ void fetch_cache_tile(Stage<BITS, G, NH>& st, const RolePtrs& rp, int Tcap, int tile, int u) {
+  using S = Stage<BITS, G, NH>;
   constexpr int kRowDw = kD * BITS / 32;  // dwords per K row == dwords per V block row
-  const uint32_t* kc = reinterpret_cast<const uint32_t*>(lc.kc) + ((size_t)h * pool.Tcap + (size_t)tile * kTile) * kRowDw;
-  const uint32_t* vc = reinterpret_cast<const uint32_t*>(lc.vc) + ((size_t)h * pool.Tcap + (size_t)tile * kTile) * kRowDw;
+  const uint32_t* base = rp.codes + (size_t)tile * kTile * kRowDw;
+  if constexpr (!S::kQuant) {
 #pragma unroll
-  for (int it = 0; it < S::kIter; ++it) {
-    const int i = tid + it * NT;
-    if (S::kItems % NT != 0 && i >= S::kItems) break;
-    if constexpr (BITS == 16) {
-      const uint4 a = reinterpret_cast<const uint4*>(kc)[i];
-      const uint4 b = reinterpret_cast<const uint4*>(vc)[i];
-      st.k[it][0] = a.x; st.k[it][1] = a.y; st.k[it][2] = a.z; st.k[it][3] = a.w;
-      st.v[it][0] = b.x; st.v[it][1] = b.y; st.v[it][2] = b.z; st.v[it][3] = b.w;
-    } else {
-      st.k[it][0] = kc[i];
-      st.v[it][0] = vc[i];
-      // K item = (token r, channel run o*kPer..): parameters per channel, group of the token
-      const int r = i / S::kRowItems, o = i % S::kRowItems;
-      const int grp = (G >= kTile) ? tile / (G / kTile) : tile * (kTile / G) + r / G;
-      const float* ks = lc.ks + ((size_t)h * (pool.Tcap / G) + grp) * kD + o * S::kPer;
-      const float* kz = lc.kz + ((size_t)h * (pool.Tcap / G) + grp) * kD + o * S::kPer;
-      // V item = (channel c, token run o*kPer..): parameters per token, group of the channel
-      const int cg = (G >= kD) ? 0 : r / G;  // r is the channel here
-      const float* vs = lc.vs + ((size_t)h * pool.Tcap + (size_t)tile * kTile + o * S::kPer) * (kD / G) + cg;
-      const float* vz = lc.vz + ((size_t)h * pool.Tcap + (size_t)tile * kTile + o * S::kPer) * (kD / G) + cg;
+    for (int it = 0; it < S::kIter; ++it) st.row[it] = reinterpret_cast<const uint4*>(base)[u + it * NH];
+  } else {
+#pragma unroll
+    for (int it = 0; it < S::kIter; ++it) st.code[it] = base[u + it * NH];
+    const int o = u % S::kRI;
+#pragma unroll
+    for (int set0 = 0; set0 < S::kSets; ++set0) {
+      // 32-row half of the tile this set belongs to (a thread with a single item has a single row)
+      const int set = (G >= 64) ? 0 : (S::kIter == 1 ? (u / S::kRI) / 32 : set0);
+      // K: parameters [group][channel], the item's channels are o*kPer.. of group (tile, set)
+      // V: parameters [token][channel group], the item's tokens are o*kPer.. of channel group `set`
+      const float *ps, *pz;
+      size_t stride;
+      if (!rp.is_v) {
+        const size_t g = (G >= kTile) ? (size_t)tile / (G / kTile) : (size_t)tile * (kTile / G) + set;
+        ps = rp.ps + g * kD + o * S::kPer;
+        pz = rp.pz + g * kD + o * S::kPer;
+        stride = 1;
+      } else {
+        const size_t t0 = (size_t)tile * kTile + o * S::kPer;
+        ps = rp.ps + t0 * (kD / G) + set;
+        pz = rp.pz + t0 * (kD / G) + set;
+        stride = kD / G;
+      }
 #pragma unroll
       for (int e = 0; e < S::kPer; ++e) {
-        st.ks[it][e] = ks[e];
-        st.kz[it][e] = kz[e];
-        st.vs[it][e] = vs[e * (kD / G)];
-        st.vz[it][e] = vz[e * (kD / G)];
+        st.ps[set0][e] = ps[e * stride];
+        st.pz[set0][e] = pz[e * stride];
       }
     }
   }
 }
 
-template <int BITS, int G, int NT>
-__device__ __forceinline__ void store_cache_tile(const Staged<BITS, G, NT>& st, uint16_t* lk, uint16_t* lv, int tid) {
-  using S = Staged<BITS, G, NT>;
+template <int BITS, int G, int NH>
+__device__ __forceinline__ void store_cache_tile(const Stage<BITS, G, NH>& st, uint16_t* lds, int u) {
+  using S = Stage<BITS, G, NH>;
+  const int r0 = u / S::kRI, o = u % S::kRI;
 #pragma unroll
   for (int it = 0; it < S::kIter; ++it) {
-    const int i = tid + it * NT;
-    if (S::kItems % NT != 0 && i >= S::kItems) break;
-    const int r = i / S::kRowItems, o = i % S::kRowItems;  // K: token r, run o;  V: channel r, token run o
-    if constexpr (BITS == 16) {
-      *reinterpret_cast<uint4*>(lk + r * kLdsStride + o * 8) = make_uint4(st.k[it][0], st.k[it][1], st.k[it][2], st.k[it][3]);
-      *reinterpret_cast<uint4*>(lv + r * kLdsStride + o * 8) = make_uint4(st.v[it][0], st.v[it][1], st.v[it][2], st.v[it][3]);
+    uint16_t* dst = lds + (r0 + it * S::kRowStep) * kLdsStride + o * S::kPer;
+    if constexpr (!S::kQuant) {
+      *reinterpret_cast<uint4*>(dst) = st.row[it];
     } else {
-      constexpr uint32_t mask = (1u << BITS) - 1u;
-      uint32_t pk[S::kPer / 2], pv[S::kPer / 2];
+      const int set = (S::kSets == 1) ? 0 : (it >= S::kIter / 2);
+      float f[S::kPer];
+      unpack_codes<BITS>(st.code[it], f);
+      uint32_t pk[S::kPer / 2];
 #pragma unroll
-      for (int e = 0; e < S::kPer; e += 2) {
-        // the cache's view of a stored element: (code - zero) * scale, then bf16
-        const float k0 = ((float)((st.k[it][0] >> (BITS * e)) & mask) - st.kz[it][e]) * st.ks[it][e];
-        const float k1 = ((float)((st.k[it][0] >> (BITS * (e + 1))) & mask) - st.kz[it][e + 1]) * st.ks[it][e + 1];
-        const float v0 = ((float)((st.v[it][0] >> (BITS * e)) & mask) - st.vz[it][e]) * st.vs[it][e];
-        const float v1 = ((float)((st.v[it][0] >> (BITS * (e + 1))) & mask) - st.vz[it][e + 1]) * st.vs[it][e + 1];
-        pk[e / 2] = pack_bf16(k0, k1);
-        pv[e / 2] = pack_bf16(v0, v1);
-      }
+      for (int e = 0; e < S::kPer; e += 2)  // the cache's view of an element: (code - zero) * scale, then bf16
+        pk[e / 2] = pack_bf16((f[e] - st.pz[set][e]) * st.ps[set][e], (f[e + 1] - st.pz[set][e + 1]) * st.ps[set][e + 1]);
 #pragma unroll
-      for (int w = 0; w < S::kPer / 8; ++w) {
-        *reinterpret_cast<uint4*>(lk + r * kLdsStride + o * S::kPer + w * 8) = make_uint4(pk[4 * w], pk[4 * w + 1], pk[4 * w + 2], pk[4 * w + 3]);
-        *reinterpret_cast<uint4*>(lv + r * kLdsStride + o * S::kPer + w * 8) = make_uint4(pv[4 * w], pv[4 * w + 1], pv[4 * w + 2], pv[4 * w + 3]);
-      }
+      for (int w = 0; w < S::kPer / 8; ++w)
+        *reinterpret_cast<uint4*>(dst + w * 8) = make_uint4(pk[4 * w], pk[4 * w + 1], pk[4 * w + 2], pk[4 * w + 3]);
     }
   }
 }
 
-// Frame tiles: 512 items of 8 bf16, item = (token r, channel run o).
-template <int NT>
-struct StagedFrame {
-  static constexpr int kIter = (512 + NT - 1) / NT;
-  uint4 k[kIter], v[kIter];
+// Frame tiles (bf16 rows as given): 512 items of 8 elements per role, item = (token i/8, channel run i%8).
+template <int NH>
+struct FrameStage {
+  static constexpr int kIter = 512 / NH;
+  uint4 row[kIter];
 };
 
-template <int NT>
-__device__ __forceinline__ void fetch_frame_tile(StagedFrame<NT>& st, const uint16_t* kh, const uint16_t* vh,
-                                                 int64_t k_st, int64_t v_st, int tile, int n, int tid) {
+template <int NH>
+__device__ __forceinline__ void fetch_frame_tile(FrameStage<NH>& st, const uint16_t* xh, int64_t x_st, int tile, int n, int u) {
 #pragma unroll
-  for (int it = 0; it < StagedFrame<NT>::kIter; ++it) {
-    const int i = tid + it * NT;
-    const int r = i >> 3, o = i & 7;
-    const int row = tile * kTile + r;
-    if (row < n) {
-      st.k[it] = *reinterpret_cast<const uint4*>(kh + (size_t)row * k_st + o * 8);
-      st.v[it] = *reinterpret_cast<const uint4*>(vh + (size_t)row * v_st + o * 8);
-    } else {  // rows past the frame: zeros (their logits are masked, their values must be finite)
-      st.k[it] = make_uint4(0, 0, 0, 0);
-      st.v[it] = make_uint4(0, 0, 0, 0);
-    }
+  for (int it = 0; it < FrameStage<NH>::kIter; ++it) {
+    const int i = u + it * NH;
+    const int row = tile * kTile + (i >> 3);
+    // rows past the frame: zeros (their logits are masked, their values must be finite)
+    st.row[it] = row < n ? *reinterpret_cast<const uint4*>(xh + (size_t)row * x_st + (i & 7) * 8) : make_uint4(0, 0, 0, 0);
   }
 }
 
-template <int NT>
-__device__ __forceinline__ void store_frame_tile(const StagedFrame<NT>& st, uint16_t* lk, uint16_t* lv, int tid) {
+template <int NH>
+__device__ __forceinline__ void store_frame_tile(const FrameStage<NH>& st, uint16_t* lds, bool is_v, int u) {
 #pragma unroll
-  for (int it = 0; it < StagedFrame<NT>::kIter; ++it) {
-    const int i = tid + it * NT;
+  for (int it = 0; it < FrameStage<NH>::kIter; ++it) {
+    const int i = u + it * NH;
     const int r = i >> 3, o = i & 7;
-    *reinterpret_cast<uint4*>(lk + r * kLdsStride + o * 8) = st.k[it];
-    // V goes in transposed: element (token r, channel 8o+e) → row 8o+e, column r
-    const uint32_t w[4] = {st.v[it].x, st.v[it].y, st.v[it].z, st.v[it].w};
+    if (!is_v) {
+      *reinterpret_cast<uint4*>(lds + r * kLdsStride + o * 8) = st.row[it];
+    } else {  // V goes in transposed: element (token r, channel 8o+e) → row 8o+e, column r
+      const uint32_t w[4] = {st.row[it].x, st.row[it].y, st.row[it].z, st.row[it].w};
 #pragma unroll
-    for (int e = 0; e < 8; ++e)
-      lv[(o * 8 + e) * kLdsStride + r] = (uint16_t)((e & 1) ? (w[e >> 1] >> 16) : (w[e >> 1] & 0xffffu));
+      for (int e = 0; e < 8; ++e)
+        lds[(o * 8 + e) * kLdsStride + r] = (uint16_t)((e & 1) ? (w[e >> 1] >> 16) : (w[e >> 1] & 0xffffu));
+    }
   }
 }
 
 // ---- the kernel ----------------------------------------------------------------------------------
-template <int BITS, int G, int NW>
+template <int BITS, int G, int NW, int QB>
 __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
-  constexpr int NT = NW * 64;
+  constexpr int NT = NW * 64, NH = NT / 2;
+  constexpr int kRowsWG = 32 * QB * NW;  // query rows per workgroup
   __shared__ __attribute__((aligned(16))) uint16_t lds_k[2][kTile * kLdsStride];
   __shared__ __attribute__((aligned(16))) uint16_t lds_v[2][kD * kLdsStride];
 
   const int H = a.pool.H, n = a.n, Tc = a.Tc, S = a.n_splits;
-  const int nqb = (n + 32 * NW - 1) / (32 * NW);
+  const int nqb = (n + kRowsWG - 1) / kRowsWG;
   const int n_groups = a.b.n_layers * H * S;
   // XCD-aware decode: ids with equal (id % 8) run on the same XCD; give them the same keys.
   const int id = blockIdx.x;
@@ -194,143 +225,202 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
 
   const LayerCache lc = layer_cache(a.pool, a.b.src_buf(lb), a.b.layer0 + lb);
   const uint16_t* qh = a.b.q[lb] + (size_t)h * a.b.q_sh;
-  const uint16_t* kh = a.b.k[lb] + (size_t)h * a.b.k_sh;
-  const uint16_t* vh = a.b.v[lb] + (size_t)h * a.b.v_sh;
+
+  // staging role of this thread: first half of the workgroup K, second half V
+  const bool is_v = tid >= NH;
+  const int u = is_v ? tid - NH : tid;
+  RolePtrs rp;
+  {
+    const size_t head_rows = (size_t)h * a.pool.Tcap;
+    rp.is_v = is_v;
+    rp.codes = reinterpret_cast<const uint32_t*>(is_v ? lc.vc : lc.kc) + head_rows * (kD * BITS / 32);
+    rp.ps = is_v ? lc.vs + head_rows * (kD / G) : lc.ks + (size_t)h * (a.pool.Tcap / G) * kD;
+    rp.pz = is_v ? lc.vz + head_rows * (kD / G) : lc.kz + (size_t)h * (a.pool.Tcap / G) * kD;
+    rp.lds[0] = is_v ? lds_v[0] : lds_k[0];
+    rp.lds[1] = is_v ? lds_v[1] : lds_k[1];
+  }
+  const uint16_t* xh = is_v ? a.b.v[lb] + (size_t)h * a.b.v_sh : a.b.k[lb] + (size_t)h * a.b.k_sh;
+  const int64_t x_st = is_v ? a.b.v_st : a.b.k_st;
 
   // tiles: cache blocks first, then the frame's own tokens (each range padded to 64 on its own)
   const int n_ct = (Tc + kTile - 1) / kTile, n_ft = (n + kTile - 1) / kTile;
   const int n_tiles = n_ct + n_ft;
   const int t_begin = (int)((long long)n_tiles * split / S), t_end = (int)((long long)n_tiles * (split + 1) / S);
 
-  // query fragments (B operand): lane holds channels 16*ks + 8*hh .. +8 of query row j, as given
+  // query fragments (B operand): lane holds channels 16*ks + 8*hh .. +8 of its query row, as given
   // (the softmax scale is applied to the fp32 logits, so no extra bf16 rounding enters)
-  const int q_row = qb * 32 * NW + wave * 32 + j;
-  const bool q_valid = q_row < n;
-  bf16x8 qf[4];
-  {
-    const uint16_t* qp = qh + (size_t)(q_valid ? q_row : n - 1) * a.b.q_st;
+  const int q_row0 = qb * kRowsWG + wave * 32 * QB;  // first row of this wave
+  bf16x8 qf[QB][4];
+#pragma unroll
+  for (int cb = 0; cb < QB; ++cb) {
+    const int q_row = q_row0 + 32 * cb + j;
+    const uint16_t* qp = qh + (size_t)min(q_row, n - 1) * a.b.q_st;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks)
-      qf[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qp + 16 * ks + 8 * hh));
+      qf[cb][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qp + 16 * ks + 8 * hh));
   }
+  // query blocks of this wave that hold at least one real row (wave-uniform)
+  const int n_cb = q_row0 >= n ? 0 : min(QB, (n - q_row0 + 31) / 32);
   const float c2 = a.qscale;  // softmax scale * log2(e): p = 2^(c2 * (logit - max))
 
-  f32x16 o0, o1;
+  f32x16 o0[QB], o1[QB];
+  float m[QB], l[QB];  // running max of the raw logits, this lane's share of the row sum
 #pragma unroll
-  for (int r = 0; r < 16; ++r) { o0[r] = 0.f; o1[r] = 0.f; }
-  float m = kNegBig, l = 0.f;  // running max of the raw logits and this lane's share of the row sum
-
-  Staged<BITS, G, NT> sc;
-  StagedFrame<NT> sf;
-  auto fetch = [&](int t) {
-    if (t < n_ct) fetch_cache_tile<BITS, G, NT>(sc, a.pool, lc, h, t, tid);
-    else fetch_frame_tile<NT>(sf, kh, vh, a.b.k_st, a.b.v_st, t - n_ct, n, tid);
-  };
-  auto store = [&](int t, int buf) {
-    if (t < n_ct) store_cache_tile<BITS, G, NT>(sc, lds_k[buf], lds_v[buf], tid);
-    else store_frame_tile<NT>(sf, lds_k[buf], lds_v[buf], tid);
-  };
-
-  if (t_begin < t_end) {
-    fetch(t_begin);
-    store(t_begin, 0);
+  for (int cb = 0; cb < QB; ++cb) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { o0[cb][r] = 0.f; o1[cb][r] = 0.f; }
+    m[cb] = kNegBig;
+    l[cb] = 0.f;
   }
   const int krow = tau(j);
+
+  // one tile of 64 tokens held in LDS buffer `buf`, of which the first `valid` are real.
+  // Order inside a half-step of 32 tokens (all independent work of a wave is interleaved so that
+  // the matrix pipe runs under the softmax arithmetic): logits of every query block, then per block
+  // softmax → its PV product; K fragments of the next half-step and the V fragments are requested
+  // from LDS before the softmax so they arrive while it runs.
+  const bool dbg_skip_compute = a.variant & 8, dbg_skip_stage = a.variant & 16;
+  auto compute = [&](int buf, int valid) {
+    if (n_cb == 0 || dbg_skip_compute) return;
+    const uint16_t* lk = lds_k[buf] + krow * kLdsStride + 8 * hh;
+    const uint16_t* lv = lds_v[buf] + j * kLdsStride + 8 * hh;
+    bf16x8 kf[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) kf[ks] = *reinterpret_cast<const bf16x8*>(lk + 16 * ks);
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      if (32 * half >= valid) break;
+      f32x16 s[QB];
+#pragma unroll
+      for (int cb = 0; cb < QB; ++cb) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[cb][r] = 0.f;
+        if (cb < n_cb) {
+#pragma unroll
+          for (int ks = 0; ks < 4; ++ks) s[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[cb][ks], s[cb], 0, 0, 0);
+        }
+      }
+      bf16x8 vf[2][2];
+#pragma unroll
+      for (int k2 = 0; k2 < 2; ++k2) {
+        vf[k2][0] = *reinterpret_cast<const bf16x8*>(lv + 32 * half + 16 * k2);
+        vf[k2][1] = *reinterpret_cast<const bf16x8*>(lv + 32 * kLdsStride + 32 * half + 16 * k2);
+      }
+      if (half == 0 && valid > 32) {
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) kf[ks] = *reinterpret_cast<const bf16x8*>(lk + 32 * kLdsStride + 16 * ks);
+      }
+#pragma unroll
+      for (int cb = 0; cb < QB; ++cb) {
+        if (cb >= n_cb) break;
+        if (valid < 32 * half + 32) {  // tokens past the end of the cache / of the frame
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            if (32 * half + 16 * (r >> 3) + 8 * hh + (r & 7) >= valid) s[cb][r] = -INFINITY;
+        }
+        // online softmax; the exponent is evaluated in base 2
+        float mx = fmaxf(s[cb][0], s[cb][1]);
+#pragma unroll
+        for (int r = 2; r < 16; r += 2) mx = fmaxf(mx, fmaxf(s[cb][r], s[cb][r + 1]));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        // the reference maximum only moves when some row's maximum grows by more than 2^kLazyLog2;
+        // until then probabilities may exceed 1 (by at most that factor), which fp32 sums and
+        // bf16 products absorb, and the accumulators need no rescaling
+        if (__any((mx - m[cb]) * c2 > kLazyLog2)) {
+          const float m_new = fmaxf(m[cb], mx);
+          const float alpha = __builtin_amdgcn_exp2f((m[cb] - m_new) * c2);
+          l[cb] *= alpha;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) { o0[cb][r] *= alpha; o1[cb][r] *= alpha; }
+          m[cb] = m_new;
+        }
+        const float mc = -m[cb] * c2;
+        float psum = l[cb];
+        uint32_t pw[8];
+#pragma unroll
+        for (int r = 0; r < 16; r += 2) {
+          const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[cb][r], c2, mc));
+          const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[cb][r + 1], c2, mc));
+          pw[r >> 1] = pack_bf16(p0, p1);
+          // row sum of the ROUNDED probabilities (what the PV product sees): v_dot2c_f32_bf16
+          psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pw[r >> 1]),
+                                                 __builtin_bit_cast(bf16x2, 0x3f803f80u), psum, false);
+        }
+        l[cb] = psum;
+        // O^T += V^T P^T: 2 contraction steps of 16 tokens; P comes straight from the accumulators
+#pragma unroll
+        for (int k2 = 0; k2 < 2; ++k2) {
+          const bf16x8 pb = __builtin_bit_cast(bf16x8, make_uint4(pw[4 * k2], pw[4 * k2 + 1], pw[4 * k2 + 2], pw[4 * k2 + 3]));
+          o0[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[k2][0], pb, o0[cb], 0, 0, 0);
+          o1[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[k2][1], pb, o1[cb], 0, 0, 0);
+        }
+      }
+    }
+  };
+
+  // Phase 1: tiles of the packed cache in [t_begin, min(t_end, n_ct)); phase 2: tiles of the frame.
+  // Each phase is software pipelined on its own: tile t+1 is fetched into registers while tile t is
+  // computed, then converted into the other LDS buffer.
   int cur = 0;
-  for (int t = t_begin; t < t_end; ++t) {
-    __syncthreads();  // tile t is in lds[cur]; everybody is done reading lds[cur^1]
-    if (t + 1 < t_end) fetch(t + 1);
-
-    const uint16_t* lk = lds_k[cur];
-    const uint16_t* lv = lds_v[cur];
-    f32x16 s0, s1;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) { s0[r] = 0.f; s1[r] = 0.f; }
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(lk + krow * kLdsStride + 16 * ks + 8 * hh);
-      const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(lk + (32 + krow) * kLdsStride + 16 * ks + 8 * hh);
-      s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qf[ks], s0, 0, 0, 0);
-      s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qf[ks], s1, 0, 0, 0);
-    }
-    // tokens past the end of the cache / of the frame in a ragged tile
-    const int valid = (t < n_ct) ? min(kTile, Tc - t * kTile) : min(kTile, n - (t - n_ct) * kTile);
-    if (valid < kTile) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int tok = 16 * (r >> 3) + 8 * hh + (r & 7);
-        if (tok >= valid) s0[r] = -INFINITY;
-        if (tok + 32 >= valid) s1[r] = -INFINITY;
+  {
+    const int c_end = min(t_end, n_ct);
+    if (t_begin < c_end) {
+      Stage<BITS, G, NH> st;
+      fetch_cache_tile<BITS, G, NH>(st, rp, a.pool.Tcap, t_begin, u);
+      store_cache_tile<BITS, G, NH>(st, rp.lds[cur], u);
+      for (int t = t_begin; t < c_end; ++t) {
+        __syncthreads();  // tile t is in lds[cur]; everybody is done reading lds[cur^1]
+        if (t + 1 < c_end && !dbg_skip_stage) fetch_cache_tile<BITS, G, NH>(st, rp, a.pool.Tcap, t + 1, u);
+        compute(cur, min(kTile, Tc - t * kTile));
+        if (t + 1 < c_end && !dbg_skip_stage) store_cache_tile<BITS, G, NH>(st, rp.lds[cur ^ 1], u);
+        cur ^= 1;
       }
     }
-    // online softmax; the exponent is evaluated in base 2
-    float mx = s0[0];
-#pragma unroll
-    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s0[r]);
-#pragma unroll
-    for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s1[r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m, mx);
-    if (__any(m_new > m)) {
-      const float alpha = __builtin_amdgcn_exp2f((m - m_new) * c2);
-      l *= alpha;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) { o0[r] *= alpha; o1[r] *= alpha; }
-      m = m_new;
-    }
-    float psum = 0.f;
-    const float mc = -m * c2;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      s0[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s0[r], c2, mc));
-      s1[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s1[r], c2, mc));
-      psum += s0[r] + s1[r];
-    }
-    l += psum;
-    // O^T += V^T P^T: 4 contraction steps of 16 tokens; P comes straight from the accumulators
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      uint32_t pw[4];
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int r = 8 * (ks & 1) + 2 * e;
-        pw[e] = (ks < 2) ? pack_bf16(s0[r], s0[r + 1]) : pack_bf16(s1[r], s1[r + 1]);
+  }
+  {
+    const int f_begin = max(t_begin, n_ct) - n_ct, f_end = t_end - n_ct;
+    if (f_begin < f_end) {
+      FrameStage<NH> st;
+      fetch_frame_tile<NH>(st, xh, x_st, f_begin, n, u);
+      store_frame_tile<NH>(st, rp.lds[cur], is_v, u);  // lds[cur] was last read two barriers ago
+      for (int t = f_begin; t < f_end; ++t) {
+        __syncthreads();
+        if (t + 1 < f_end && !dbg_skip_stage) fetch_frame_tile<NH>(st, xh, x_st, t + 1, n, u);
+        compute(cur, min(kTile, n - t * kTile));
+        if (t + 1 < f_end && !dbg_skip_stage) store_frame_tile<NH>(st, rp.lds[cur ^ 1], is_v, u);
+        cur ^= 1;
       }
-      const bf16x8 pb = __builtin_bit_cast(bf16x8, make_uint4(pw[0], pw[1], pw[2], pw[3]));
-      const bf16x8 v0 = *reinterpret_cast<const bf16x8*>(lv + j * kLdsStride + 16 * ks + 8 * hh);
-      const bf16x8 v1 = *reinterpret_cast<const bf16x8*>(lv + (32 + j) * kLdsStride + 16 * ks + 8 * hh);
-      o0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v0, pb, o0, 0, 0, 0);
-      o1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v1, pb, o1, 0, 0, 0);
     }
-
-    if (t + 1 < t_end) store(t + 1, cur ^ 1);
-    cur ^= 1;
   }
 
-  l += __shfl_xor(l, 32);  // the two lane halves saw disjoint tokens of the same query
-  if (!q_valid) return;
-  // accumulator register r of o0 (o1) is channel 8*(r/4) + 4*hh + r%4 (+32) of query row j
-  if (S == 1) {
-    const float inv = 1.0f / l;
-    uint16_t* op = a.b.out[lb] + ((size_t)h * n + q_row) * kD;
+  // accumulator register r of o0 (o1) is channel 8*(r/4) + 4*hh + r%4 (+32) of the lane's query row
 #pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4) {
-      const int c = 8 * q4 + 4 * hh;
-      *reinterpret_cast<uint2*>(op + c) = make_uint2(pack_bf16(o0[4 * q4] * inv, o0[4 * q4 + 1] * inv),
-                                                     pack_bf16(o0[4 * q4 + 2] * inv, o0[4 * q4 + 3] * inv));
-      *reinterpret_cast<uint2*>(op + 32 + c) = make_uint2(pack_bf16(o1[4 * q4] * inv, o1[4 * q4 + 1] * inv),
-                                                          pack_bf16(o1[4 * q4 + 2] * inv, o1[4 * q4 + 3] * inv));
-    }
-  } else {
-    const size_t row = (((size_t)split * a.b.n_layers + lb) * H + h) * n + q_row;
-    float* op = a.ws.attn_o + row * kD;
+  for (int cb = 0; cb < QB; ++cb) {
+    const int q_row = q_row0 + 32 * cb + j;
+    const float lsum = l[cb] + __shfl_xor(l[cb], 32);  // the two lane halves saw disjoint tokens
+    if (q_row >= n) continue;
+    if (S == 1) {
+      const float inv = 1.0f / lsum;
+      uint16_t* op = a.b.out[lb] + ((size_t)h * n + q_row) * kD;
 #pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4) {
-      const int c = 8 * q4 + 4 * hh;
-      *reinterpret_cast<float4*>(op + c) = make_float4(o0[4 * q4], o0[4 * q4 + 1], o0[4 * q4 + 2], o0[4 * q4 + 3]);
-      *reinterpret_cast<float4*>(op + 32 + c) = make_float4(o1[4 * q4], o1[4 * q4 + 1], o1[4 * q4 + 2], o1[4 * q4 + 3]);
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const int c = 8 * q4 + 4 * hh;
+        *reinterpret_cast<uint2*>(op + c) = make_uint2(pack_bf16(o0[cb][4 * q4] * inv, o0[cb][4 * q4 + 1] * inv),
+                                                       pack_bf16(o0[cb][4 * q4 + 2] * inv, o0[cb][4 * q4 + 3] * inv));
+        *reinterpret_cast<uint2*>(op + 32 + c) = make_uint2(pack_bf16(o1[cb][4 * q4] * inv, o1[cb][4 * q4 + 1] * inv),
+                                                            pack_bf16(o1[cb][4 * q4 + 2] * inv, o1[cb][4 * q4 + 3] * inv));
+      }
+    } else {
+      const size_t row = (((size_t)split * a.b.n_layers + lb) * H + h) * n + q_row;
+      float* op = a.ws.attn_o + row * kD;
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const int c = 8 * q4 + 4 * hh;
+        *reinterpret_cast<float4*>(op + c) = make_float4(o0[cb][4 * q4], o0[cb][4 * q4 + 1], o0[cb][4 * q4 + 2], o0[cb][4 * q4 + 3]);
+        *reinterpret_cast<float4*>(op + 32 + c) = make_float4(o1[cb][4 * q4], o1[cb][4 * q4 + 1], o1[cb][4 * q4 + 2], o1[cb][4 * q4 + 3]);
+      }
+      if (hh == 0) *reinterpret_cast<float2*>(a.ws.attn_ml + row * 2) = make_float2(m[cb] * c2, lsum);
     }
-    if (hh == 0) *reinterpret_cast<float2*>(a.ws.attn_ml + row * 2) = make_float2(m * c2, l);
   }
 }
 
@@ -359,13 +449,12 @@ __global__ __launch_bounds__(256) void combine_kernel(const AttendArgs a) {
       make_uint2(pack_bf16(acc[0] * inv, acc[1] * inv), pack_bf16(acc[2] * inv, acc[3] * inv));
 }
 
-template <int BITS, int G>
+template <int BITS, int G, int NW, int QB>
 static hipError_t launch_attend_t(const AttendArgs& a, hipStream_t stream) {
-  constexpr int NW = 4;
-  const int nqb = (a.n + 32 * NW - 1) / (32 * NW);
+  const int nqb = (a.n + 32 * QB * NW - 1) / (32 * QB * NW);
   const int n_groups = a.b.n_layers * a.pool.H * a.n_splits;
   const int grid = ((n_groups + 7) / 8) * 8 * nqb;
-  hipLaunchKernelGGL((attend_kernel<BITS, G, NW>), dim3(grid), dim3(NW * 64), 0, stream, a);
+  hipLaunchKernelGGL((attend_kernel<BITS, G, NW, QB>), dim3(grid), dim3(NW * 64), 0, stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (a.n_splits > 1) {
@@ -376,13 +465,24 @@ static hipError_t launch_attend_t(const AttendArgs& a, hipStream_t stream) {
   return e;
 }
 
+template <int BITS, int G>
+static hipError_t launch_attend_v(const AttendArgs& a, hipStream_t stream) {
+  switch (a.variant & 7) {
+    case 1: return launch_attend_t<BITS, G, 4, 1>(a, stream);
+    case 2: return launch_attend_t<BITS, G, 8, 1>(a, stream);
+    default: return launch_attend_t<BITS, G, 4, 2>(a, stream);
+  }
+}
+
+int attend_rows_per_workgroup(int variant) { return (variant & 7) == 1 ? 128 : 256; }
+
 hipError_t launch_attend(const AttendArgs& a, hipStream_t stream) {
   const int bits = a.pool.bits, G = a.pool.G;
-  if (bits == 16) return launch_attend_t<16, 64>(a, stream);
-  if (bits == 4 && G == 64) return launch_attend_t<4, 64>(a, stream);
-  if (bits == 4 && G == 32) return launch_attend_t<4, 32>(a, stream);
-  if (bits == 2 && G == 64) return launch_attend_t<2, 64>(a, stream);
-  if (bits == 2 && G == 32) return launch_attend_t<2, 32>(a, stream);
+  if (bits == 16) return launch_attend_v<16, 64>(a, stream);
+  if (bits == 4 && G == 64) return launch_attend_v<4, 64>(a, stream);
+  if (bits == 4 && G == 32) return launch_attend_v<4, 32>(a, stream);
+  if (bits == 2 && G == 64) return launch_attend_v<2, 64>(a, stream);
+  if (bits == 2 && G == 32) return launch_attend_v<2, 32>(a, stream);
   return hipErrorInvalidValue;
 }
 

@@ -34,11 +34,18 @@ struct LayerState {
 struct xsv_ctx {
   xsv_config cfg;
   hipStream_t stream;
+  // xsv_step runs the score/select/re-quantize chain on `side` while the attention kernel runs on
+  // `stream` (the chain only reads what attention reads and writes the OTHER cache buffer)
+  hipStream_t side = nullptr;
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+  hipStream_t work = nullptr;  // stream the score/quantize launchers currently enqueue on
+  bool overlap = true;
   CachePool pool;
   Workspace ws;
   std::vector<LayerState> layers;
   std::vector<void*> allocs;
   int splits_single = 0, splits_batched = 0;
+  int attend_variant = 0;
   int max_splits = 1;
   size_t part_rows = 0;  // rows the partial-output workspace holds
   int n_cu = 256;
@@ -76,6 +83,11 @@ int dev_alloc(xsv_ctx* ctx, T** out, size_t count, bool zero) {
 void free_all(xsv_ctx* ctx) {
   for (void* p : ctx->allocs) (void)hipFree(p);
   ctx->allocs.clear();
+  if (ctx->side) (void)hipStreamDestroy(ctx->side);
+  if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
+  if (ctx->ev_join) (void)hipEventDestroy(ctx->ev_join);
+  ctx->side = nullptr;
+  ctx->ev_fork = ctx->ev_join = nullptr;
 }
 
 // What a step does to the cache length (paper Sec. 3.2: prune once T exceeds the budget; first and
@@ -111,10 +123,13 @@ int choose_splits(const xsv_ctx* ctx, int n_layers, int Tc, int requested) {
   const int n_tiles = (Tc + kTile - 1) / kTile + (c.tokens_per_frame + kTile - 1) / kTile;
   int s = requested;
   if (s <= 0) {
-    const int wgs = ((c.tokens_per_frame + 127) / 128) * c.n_heads * n_layers;
-    // aim at ~2 workgroups per compute unit, never ranges shorter than 8 tiles
-    s = (2 * ctx->n_cu + wgs - 1) / wgs;
-    s = std::min(s, std::max(1, n_tiles / 8));
+    const int rows = attend_rows_per_workgroup(ctx->attend_variant);
+    const int wgs = ((c.tokens_per_frame + rows - 1) / rows) * c.n_heads * n_layers;
+    // fill the workgroup slots of the chip (2 per compute unit; 1 for the 8-wave variant) in ONE
+    // round, never with ranges shorter than 4 tiles
+    const int slots = ((ctx->attend_variant & 7) == 2 ? 1 : 2) * ctx->n_cu;
+    s = std::max(1, slots / wgs);
+    s = std::min(s, std::max(1, n_tiles / 4));
   }
   const size_t rows_per_split = (size_t)n_layers * c.n_heads * c.tokens_per_frame;
   s = std::max(1, std::min({s, ctx->max_splits, n_tiles, (int)(ctx->part_rows / rows_per_split)}));
@@ -161,6 +176,7 @@ int do_attend(xsv_ctx* ctx, int layer0, int n_layers, const xsv_tensor* q, const
   a.ws = ctx->ws;
   a.Tc = ctx->layers[layer0].T;
   a.n = ctx->cfg.tokens_per_frame;
+  a.variant = ctx->attend_variant;
   a.n_splits = choose_splits(ctx, n_layers, a.Tc, splits_req);
   a.qscale = ctx->cfg.softmax_scale * 1.4426950408889634f;
   if (launch_attend(a, ctx->stream) != hipSuccess) return hip_fail(ctx);
@@ -172,10 +188,10 @@ int do_score_prune(xsv_ctx* ctx, int layer0, int n_layers, const xsv_tensor* q) 
   const PrunePlan p = plan_for(ctx->cfg, ctx->layers[layer0]);
   int32_t* keep = ctx->ws.keep + (size_t)layer0 * ctx->ws.scores_stride;
   if (!p.prune) {
-    if (launch_fill_keep(keep, ctx->ws.scores_stride, n_layers, p.T, 0, 0, true, ctx->stream) != hipSuccess) return hip_fail(ctx);
+    if (launch_fill_keep(keep, ctx->ws.scores_stride, n_layers, p.T, 0, 0, true, ctx->work) != hipSuccess) return hip_fail(ctx);
   } else if (!p.score) {
     // k == 0: first ∪ current;  k == P: everything (cannot happen once T > budget, kept for completeness)
-    if (launch_fill_keep(keep, ctx->ws.scores_stride, n_layers, p.T_first, p.P, p.T_cur, p.k == p.P, ctx->stream) != hipSuccess)
+    if (launch_fill_keep(keep, ctx->ws.scores_stride, n_layers, p.T_first, p.P, p.T_cur, p.k == p.P, ctx->work) != hipSuccess)
       return hip_fail(ctx);
   } else {
     ScoreArgs s{};
@@ -190,15 +206,15 @@ int do_score_prune(xsv_ctx* ctx, int layer0, int n_layers, const xsv_tensor* q) 
     s.T_first = p.T_first;
     s.P = p.P;
     s.k_plain = nullptr;
-    if (launch_pool_query(s, ctx->stream) != hipSuccess) return hip_fail(ctx);
-    if (launch_score(s, ctx->stream) != hipSuccess) return hip_fail(ctx);
+    if (launch_pool_query(s, ctx->work) != hipSuccess) return hip_fail(ctx);
+    if (launch_score(s, ctx->work) != hipSuccess) return hip_fail(ctx);
     SelectArgs sel{};
     sel.scores = ctx->ws.scores + (size_t)layer0 * ctx->ws.scores_stride;
     sel.keep = keep;
     sel.scores_stride = sel.keep_stride = ctx->ws.scores_stride;
     sel.n_layers = n_layers;
     sel.P = p.P; sel.k = p.k; sel.T_first = p.T_first; sel.T_cur = p.T_cur;
-    if (launch_select(sel, ctx->stream) != hipSuccess) return hip_fail(ctx);
+    if (launch_select(sel, ctx->work) != hipSuccess) return hip_fail(ctx);
   }
   for (int i = 0; i < n_layers; ++i) {
     LayerState& L = ctx->layers[layer0 + i];
@@ -220,7 +236,7 @@ int do_quantize(xsv_ctx* ctx, int layer0, int n_layers, const xsv_tensor* k, con
   r.n = ctx->cfg.tokens_per_frame;
   r.Tn = ctx->layers[layer0].pending_Tn;
   r.frame_id = ctx->layers[layer0].frames;
-  if (launch_requant(r, ctx->stream) != hipSuccess) return hip_fail(ctx);
+  if (launch_requant(r, ctx->work) != hipSuccess) return hip_fail(ctx);
   for (int i = 0; i < n_layers; ++i) {
     LayerState& L = ctx->layers[layer0 + i];
     L.T = r.Tn;
@@ -296,7 +312,17 @@ int xsv_create(const xsv_config* cfg, void* hip_stream, xsv_ctx** out) {
   if (!ctx) return XSV_ERR_OOM;
   ctx->cfg = c;
   ctx->stream = static_cast<hipStream_t>(hip_stream);
+  ctx->work = ctx->stream;
   ctx->layers.resize(c.n_layers);
+  if (hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) != hipSuccess ||
+      hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming) != hipSuccess) {
+    if (ctx->side) (void)hipStreamDestroy(ctx->side);
+    if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
+    if (ctx->ev_join) (void)hipEventDestroy(ctx->ev_join);
+    delete ctx;
+    return XSV_ERR_HIP;
+  }
   int dev = 0;
   hipDeviceProp_t prop;
   if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) {
@@ -350,6 +376,7 @@ int xsv_create(const xsv_config* cfg, void* hip_stream, xsv_ctx** out) {
 int xsv_destroy(xsv_ctx* ctx) {
   if (!ctx) return XSV_OK;
   (void)hipStreamSynchronize(ctx->stream);
+  if (ctx->side) (void)hipStreamSynchronize(ctx->side);
   free_all(ctx);
   delete ctx;
   return XSV_OK;
@@ -366,6 +393,12 @@ int xsv_set_attend_splits(xsv_ctx* ctx, int per_layer_calls, int batched_calls) 
   if (!ctx || per_layer_calls < 0 || per_layer_calls > 16 || batched_calls < 0 || batched_calls > 16) return XSV_ERR_ARG;
   ctx->splits_single = per_layer_calls;
   ctx->splits_batched = batched_calls;
+  return XSV_OK;
+}
+
+int xsv_set_attend_variant(xsv_ctx* ctx, int variant) {
+  if (!ctx || variant < 0 || variant > 31) return XSV_ERR_ARG;
+  ctx->attend_variant = variant;
   return XSV_OK;
 }
 
@@ -393,11 +426,37 @@ int xsv_quantize(xsv_ctx* ctx, int layer, xsv_tensor k_new, xsv_tensor v_new) {
   return do_quantize(ctx, layer, 1, &k_new, &v_new);
 }
 
+// attention on the context's stream, score → select → re-quantize concurrently on the side stream;
+// on return the context's stream is ordered after both
+static int step_layers(xsv_ctx* ctx, int layer0, int n_layers, const xsv_tensor* q, const xsv_tensor* k,
+                       const xsv_tensor* v, void* const* out, int splits) {
+  const bool fork = ctx->overlap;
+  if (fork) {
+    if (hipEventRecord(ctx->ev_fork, ctx->stream) != hipSuccess || hipStreamWaitEvent(ctx->side, ctx->ev_fork, 0) != hipSuccess)
+      return hip_fail(ctx);
+  }
+  int rc = do_attend(ctx, layer0, n_layers, q, k, v, out, splits);
+  if (rc == XSV_OK) {
+    ctx->work = fork ? ctx->side : ctx->stream;
+    rc = do_score_prune(ctx, layer0, n_layers, q);
+    if (rc == XSV_OK) rc = do_quantize(ctx, layer0, n_layers, k, v);
+    ctx->work = ctx->stream;
+  }
+  if (fork) {  // join even after an error so the streams stay ordered
+    if (hipEventRecord(ctx->ev_join, ctx->side) != hipSuccess || hipStreamWaitEvent(ctx->stream, ctx->ev_join, 0) != hipSuccess)
+      return hip_fail(ctx);
+  }
+  return rc;
+}
+
 int xsv_step(xsv_ctx* ctx, int layer, xsv_tensor q, xsv_tensor k_new, xsv_tensor v_new, void* out) {
-  int rc = xsv_dequant_attend(ctx, layer, q, k_new, v_new, out);
+  int rc = check_layer(ctx, layer);
   if (rc != XSV_OK) return rc;
-  if ((rc = xsv_score_prune(ctx, layer, q)) != XSV_OK) return rc;
-  return xsv_quantize(ctx, layer, k_new, v_new);
+  if (ctx->layers[layer].phase != kIdle) return XSV_ERR_STATE;
+  if ((rc = check_capacity(ctx, layer)) != XSV_OK) return rc;
+  if (!tensor_ok(q) || !tensor_ok(k_new) || !tensor_ok(v_new) || !out) return XSV_ERR_ARG;
+  void* outs[1] = {out};
+  return step_layers(ctx, layer, 1, &q, &k_new, &v_new, outs, ctx->splits_single);
 }
 
 int xsv_step_all_layers(xsv_ctx* ctx, const xsv_tensor* q, const xsv_tensor* k_new, const xsv_tensor* v_new,
@@ -409,12 +468,17 @@ int xsv_step_all_layers(xsv_ctx* ctx, const xsv_tensor* q, const xsv_tensor* k_n
   for (int l = 0; l < L; ++l) {
     const LayerState& a = ctx->layers[l];
     if (a.phase != kIdle || a.T != ctx->layers[0].T || a.frames != ctx->layers[0].frames) return XSV_ERR_STATE;
+    if (!tensor_ok(q[l]) || !tensor_ok(k_new[l]) || !tensor_ok(v_new[l]) || !out[l]) return XSV_ERR_ARG;
   }
   int rc = check_capacity(ctx, 0);
   if (rc != XSV_OK) return rc;
-  if ((rc = do_attend(ctx, 0, L, q, k_new, v_new, out, ctx->splits_batched)) != XSV_OK) return rc;
-  if ((rc = do_score_prune(ctx, 0, L, q)) != XSV_OK) return rc;
-  return do_quantize(ctx, 0, L, k_new, v_new);
+  return step_layers(ctx, 0, L, q, k_new, v_new, out, ctx->splits_batched);
+}
+
+int xsv_set_overlap(xsv_ctx* ctx, int enabled) {
+  if (!ctx) return XSV_ERR_ARG;
+  ctx->overlap = enabled != 0;
+  return XSV_OK;
 }
 
 int xsv_cache_len(xsv_ctx* ctx, int layer, int32_t* T) {

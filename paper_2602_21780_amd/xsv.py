@@ -42,7 +42,7 @@ class xsv_tensor(C.Structure):
 # every symbol include/xsv.h declares
 EXPORTS = (
     "xsv_create", "xsv_destroy", "xsv_reset", "xsv_dequant_attend", "xsv_score_prune", "xsv_quantize",
-    "xsv_step", "xsv_step_all_layers", "xsv_set_attend_splits", "xsv_cache_len", "xsv_cache_export",
+    "xsv_step", "xsv_step_all_layers", "xsv_set_attend_splits", "xsv_set_attend_variant", "xsv_set_overlap", "xsv_cache_len", "xsv_cache_export",
     "xsv_cache_import", "xsv_last_selection", "xsv_quantize_k", "xsv_quantize_v", "xsv_score",
     "xsv_topk_keep", "xsv_strerror",
 )
@@ -69,6 +69,8 @@ def lib():
         L.xsv_step.argtypes = [vp, i32, T, T, T, vp]
         L.xsv_step_all_layers.argtypes = [vp, C.POINTER(T), C.POINTER(T), C.POINTER(T), C.POINTER(vp)]
         L.xsv_set_attend_splits.argtypes = [vp, i32, i32]
+        L.xsv_set_attend_variant.argtypes = [vp, i32]
+        L.xsv_set_overlap.argtypes = [vp, i32]
         L.xsv_cache_len.argtypes = [vp, i32, C.POINTER(C.c_int32)]
         L.xsv_cache_export.argtypes = [vp, i32] + [vp] * 10
         L.xsv_cache_import.argtypes = [vp, i32, C.c_int32, C.c_int32] + [vp] * 10
@@ -163,6 +165,12 @@ class Context:
 
     def set_attend_splits(self, per_layer_calls=0, batched_calls=0):
         _check(lib().xsv_set_attend_splits(self._h, per_layer_calls, batched_calls), "xsv_set_attend_splits")
+
+    def set_attend_variant(self, variant):
+        _check(lib().xsv_set_attend_variant(self._h, variant), "xsv_set_attend_variant")
+
+    def set_overlap(self, enabled):
+        _check(lib().xsv_set_overlap(self._h, int(enabled)), "xsv_set_overlap")
 
     def _out(self, q, out):
         if out is None:
