@@ -46,6 +46,7 @@ def main():
     ap.add_argument("--mode", choices=["layerwise", "batched"], default="layerwise")
     ap.add_argument("--splits", type=int, default=0, help="key ranges per attention launch (0 = auto)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--no-overlap", action="store_true", help="run the prune chain after attention on one stream")
     ap.add_argument("--stage-frames", type=int, default=6, help="frames of the per-stage event-timed pass")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -72,6 +73,8 @@ def main():
     out = torch.empty((L, spec.n_heads, n, spec.head_dim), dtype=torch.bfloat16, device=dev)
     ctx = xsv.Context.from_spec(spec)
     ctx.set_attend_splits(args.splits, args.splits)
+    if args.no_overlap:
+        ctx.set_overlap(False)
     packed = [ctx.pack_layers(q, k, v, out) for (q, k, v) in frames]
     torch.cuda.synchronize()
 

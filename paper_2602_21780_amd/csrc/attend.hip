@@ -28,6 +28,7 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr int kLdsStride = 72;  // bf16 elements per LDS row: 64 + 8 pad (144 B, keeps 16 B alignment)
+constexpr int kLdsTile = 64 * kLdsStride;  // elements of one K (or V) tile in LDS
 constexpr float kNegBig = -1.0e30f;
 constexpr float kLazyLog2 = 8.0f;  // headroom of the lazily updated softmax reference, in powers of two
 
@@ -96,7 +97,7 @@ struct RolePtrs {      // what distinguishes the K half from the V half
   const uint32_t* codes;  // packed tile base of (layer, head): row-major [Tcap rows][row dwords]
   const float* ps;        // parameter arrays of (layer, head)
   const float* pz;
-  uint16_t* lds[2];       // the two LDS tiles of this role
+  uint16_t* lds;          // first of the two LDS tiles of this role (the second follows it)
   bool is_v;
 };
 
@@ -164,48 +165,79 @@ __device__ __forceinline__ void store_cache_tile(const Stage<BITS, G, NH>& st, u
   }
 }
 
-// Frame tiles (bf16 rows as given): 512 items of 8 elements per role, item = (token i/8, channel run i%8).
+// Frame tiles (bf16 rows as given).  K half: 512 items of 16 bytes, item = (token i/8, channel run
+// i%8), copied as they are.  V half: the tile must land transposed ([channel][token]); an item is
+// (token octet i/32, channel pair i%32): eight 4-byte loads down the token axis (coalesced across
+// the 32 channel pairs of a row), two byte-permutes per register pair, and two 16-byte LDS writes.
 template <int NH>
 struct FrameStage {
-  static constexpr int kIter = 512 / NH;
-  uint4 row[kIter];
+  static constexpr int kIterK = 512 / NH;  // 16-byte items per K thread
+  static constexpr int kIterV = 256 / NH;  // 8-dword items per V thread
+  static_assert(kIterK * 4 == kIterV * 8, "both roles stage the same number of registers");
+  uint32_t w[kIterK * 4];
 };
 
 template <int NH>
-__device__ __forceinline__ void fetch_frame_tile(FrameStage<NH>& st, const uint16_t* xh, int64_t x_st, int tile, int n, int u) {
+__device__ __forceinline__ void fetch_frame_tile(FrameStage<NH>& st, const uint16_t* xh, int64_t x_st, bool is_v, int tile,
+                                                 int n, int u) {
+  using F = FrameStage<NH>;
+  if (!is_v) {
 #pragma unroll
-  for (int it = 0; it < FrameStage<NH>::kIter; ++it) {
-    const int i = u + it * NH;
-    const int row = tile * kTile + (i >> 3);
-    // rows past the frame: zeros (their logits are masked, their values must be finite)
-    st.row[it] = row < n ? *reinterpret_cast<const uint4*>(xh + (size_t)row * x_st + (i & 7) * 8) : make_uint4(0, 0, 0, 0);
+    for (int it = 0; it < F::kIterK; ++it) {
+      const int i = u + it * NH;
+      const int row = tile * kTile + (i >> 3);
+      // rows past the frame: zeros (their logits are masked, their values must be finite)
+      const uint4 v = row < n ? *reinterpret_cast<const uint4*>(xh + (size_t)row * x_st + (i & 7) * 8) : make_uint4(0, 0, 0, 0);
+      st.w[4 * it] = v.x; st.w[4 * it + 1] = v.y; st.w[4 * it + 2] = v.z; st.w[4 * it + 3] = v.w;
+    }
+  } else {
+#pragma unroll
+    for (int it = 0; it < F::kIterV; ++it) {
+      const int i = u + it * NH;
+      const int c2 = i & 31, tq = i >> 5;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int row = tile * kTile + 8 * tq + e;
+        st.w[8 * it + e] = row < n ? *reinterpret_cast<const uint32_t*>(xh + (size_t)row * x_st + 2 * c2) : 0u;
+      }
+    }
   }
 }
 
 template <int NH>
 __device__ __forceinline__ void store_frame_tile(const FrameStage<NH>& st, uint16_t* lds, bool is_v, int u) {
+  using F = FrameStage<NH>;
+  if (!is_v) {
 #pragma unroll
-  for (int it = 0; it < FrameStage<NH>::kIter; ++it) {
-    const int i = u + it * NH;
-    const int r = i >> 3, o = i & 7;
-    if (!is_v) {
-      *reinterpret_cast<uint4*>(lds + r * kLdsStride + o * 8) = st.row[it];
-    } else {  // V goes in transposed: element (token r, channel 8o+e) → row 8o+e, column r
-      const uint32_t w[4] = {st.row[it].x, st.row[it].y, st.row[it].z, st.row[it].w};
+    for (int it = 0; it < F::kIterK; ++it) {
+      const int i = u + it * NH;
+      *reinterpret_cast<uint4*>(lds + (i >> 3) * kLdsStride + (i & 7) * 8) =
+          make_uint4(st.w[4 * it], st.w[4 * it + 1], st.w[4 * it + 2], st.w[4 * it + 3]);
+    }
+  } else {
 #pragma unroll
-      for (int e = 0; e < 8; ++e)
-        lds[(o * 8 + e) * kLdsStride + r] = (uint16_t)((e & 1) ? (w[e >> 1] >> 16) : (w[e >> 1] & 0xffffu));
+    for (int it = 0; it < F::kIterV; ++it) {
+      const int i = u + it * NH;
+      const int c2 = i & 31, tq = i >> 5;
+      uint32_t lo[4], hi[4];  // tokens 8tq.. of channel 2*c2 and of channel 2*c2+1
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        lo[k] = __builtin_amdgcn_perm(st.w[8 * it + 2 * k + 1], st.w[8 * it + 2 * k], 0x05040100u);
+        hi[k] = __builtin_amdgcn_perm(st.w[8 * it + 2 * k + 1], st.w[8 * it + 2 * k], 0x07060302u);
+      }
+      *reinterpret_cast<uint4*>(lds + (2 * c2) * kLdsStride + 8 * tq) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+      *reinterpret_cast<uint4*>(lds + (2 * c2 + 1) * kLdsStride + 8 * tq) = make_uint4(hi[0], hi[1], hi[2], hi[3]);
     }
   }
 }
 
 // ---- the kernel ----------------------------------------------------------------------------------
-template <int BITS, int G, int NW, int QB>
+template <int BITS, int G, int NW, int QB, int DBG = 0>
 __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
   constexpr int NT = NW * 64, NH = NT / 2;
   constexpr int kRowsWG = 32 * QB * NW;  // query rows per workgroup
-  __shared__ __attribute__((aligned(16))) uint16_t lds_k[2][kTile * kLdsStride];
-  __shared__ __attribute__((aligned(16))) uint16_t lds_v[2][kD * kLdsStride];
+  __shared__ __attribute__((aligned(16))) uint16_t lds_k[2][kLdsTile];
+  __shared__ __attribute__((aligned(16))) uint16_t lds_v[2][kLdsTile];
 
   const int H = a.pool.H, n = a.n, Tc = a.Tc, S = a.n_splits;
   const int nqb = (n + kRowsWG - 1) / kRowsWG;
@@ -222,6 +254,11 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int j = lane & 31, hh = lane >> 5;
+  if (a.dbg && tid == 0) {
+    a.dbg[4 * id] = wall_clock64();
+    a.dbg[4 * id + 2] = __builtin_amdgcn_s_getreg((4) | (0 << 6) | (31 << 11));
+    a.dbg[4 * id + 3] = __builtin_amdgcn_s_getreg((20) | (0 << 6) | (31 << 11));
+  }
 
   const LayerCache lc = layer_cache(a.pool, a.b.src_buf(lb), a.b.layer0 + lb);
   const uint16_t* qh = a.b.q[lb] + (size_t)h * a.b.q_sh;
@@ -236,16 +273,16 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
     rp.codes = reinterpret_cast<const uint32_t*>(is_v ? lc.vc : lc.kc) + head_rows * (kD * BITS / 32);
     rp.ps = is_v ? lc.vs + head_rows * (kD / G) : lc.ks + (size_t)h * (a.pool.Tcap / G) * kD;
     rp.pz = is_v ? lc.vz + head_rows * (kD / G) : lc.kz + (size_t)h * (a.pool.Tcap / G) * kD;
-    rp.lds[0] = is_v ? lds_v[0] : lds_k[0];
-    rp.lds[1] = is_v ? lds_v[1] : lds_k[1];
+    rp.lds = is_v ? lds_v[0] : lds_k[0];
   }
   const uint16_t* xh = is_v ? a.b.v[lb] + (size_t)h * a.b.v_sh : a.b.k[lb] + (size_t)h * a.b.k_sh;
   const int64_t x_st = is_v ? a.b.v_st : a.b.k_st;
 
-  // tiles: cache blocks first, then the frame's own tokens (each range padded to 64 on its own)
+  // tiles: cache blocks, then the frame's own tokens (each range padded to 64 on its own).  A key
+  // range takes an equal share of BOTH kinds, so that every range costs the same.
   const int n_ct = (Tc + kTile - 1) / kTile, n_ft = (n + kTile - 1) / kTile;
-  const int n_tiles = n_ct + n_ft;
-  const int t_begin = (int)((long long)n_tiles * split / S), t_end = (int)((long long)n_tiles * (split + 1) / S);
+  const int c_begin = (int)((long long)n_ct * split / S), c_end = (int)((long long)n_ct * (split + 1) / S);
+  const int f_begin = (int)((long long)n_ft * split / S), f_end = (int)((long long)n_ft * (split + 1) / S);
 
   // query fragments (B operand): lane holds channels 16*ks + 8*hh .. +8 of its query row, as given
   // (the softmax scale is applied to the fp32 logits, so no extra bf16 rounding enters)
@@ -297,7 +334,7 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
         for (int r = 0; r < 16; ++r) s[cb][r] = 0.f;
         if (cb < n_cb) {
 #pragma unroll
-          for (int ks = 0; ks < 4; ++ks) s[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[cb][ks], s[cb], 0, 0, 0);
+          for (int ks = 0; ks < (DBG == 2 ? 1 : 4); ++ks) s[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[cb][ks], s[cb], 0, 0, 0);
         }
       }
       bf16x8 vf[2][2];
@@ -339,8 +376,8 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
         uint32_t pw[8];
 #pragma unroll
         for (int r = 0; r < 16; r += 2) {
-          const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[cb][r], c2, mc));
-          const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[cb][r + 1], c2, mc));
+          const float p0 = DBG == 1 ? __builtin_fmaf(s[cb][r], c2, mc) : __builtin_amdgcn_exp2f(__builtin_fmaf(s[cb][r], c2, mc));
+          const float p1 = DBG == 1 ? __builtin_fmaf(s[cb][r + 1], c2, mc) : __builtin_amdgcn_exp2f(__builtin_fmaf(s[cb][r + 1], c2, mc));
           pw[r >> 1] = pack_bf16(p0, p1);
           // row sum of the ROUNDED probabilities (what the PV product sees): v_dot2c_f32_bf16
           psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pw[r >> 1]),
@@ -349,7 +386,7 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
         l[cb] = psum;
         // O^T += V^T P^T: 2 contraction steps of 16 tokens; P comes straight from the accumulators
 #pragma unroll
-        for (int k2 = 0; k2 < 2; ++k2) {
+        for (int k2 = 0; k2 < (DBG == 3 ? 1 : 2); ++k2) {
           const bf16x8 pb = __builtin_bit_cast(bf16x8, make_uint4(pw[4 * k2], pw[4 * k2 + 1], pw[4 * k2 + 2], pw[4 * k2 + 3]));
           o0[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[k2][0], pb, o0[cb], 0, 0, 0);
           o1[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[k2][1], pb, o1[cb], 0, 0, 0);
@@ -357,39 +394,32 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
       }
     }
   };
-
-  // Phase 1: tiles of the packed cache in [t_begin, min(t_end, n_ct)); phase 2: tiles of the frame.
-  // Each phase is software pipelined on its own: tile t+1 is fetched into registers while tile t is
-  // computed, then converted into the other LDS buffer.
+  // Phase 1: this range's tiles of the packed cache; phase 2: its tiles of the frame.  Each phase is
+  // software pipelined on its own: tile t+1 is fetched into registers while tile t is computed,
+  // then converted into the other LDS buffer.
   int cur = 0;
-  {
-    const int c_end = min(t_end, n_ct);
-    if (t_begin < c_end) {
-      Stage<BITS, G, NH> st;
-      fetch_cache_tile<BITS, G, NH>(st, rp, a.pool.Tcap, t_begin, u);
-      store_cache_tile<BITS, G, NH>(st, rp.lds[cur], u);
-      for (int t = t_begin; t < c_end; ++t) {
-        __syncthreads();  // tile t is in lds[cur]; everybody is done reading lds[cur^1]
-        if (t + 1 < c_end && !dbg_skip_stage) fetch_cache_tile<BITS, G, NH>(st, rp, a.pool.Tcap, t + 1, u);
-        compute(cur, min(kTile, Tc - t * kTile));
-        if (t + 1 < c_end && !dbg_skip_stage) store_cache_tile<BITS, G, NH>(st, rp.lds[cur ^ 1], u);
-        cur ^= 1;
-      }
+  if (c_begin < c_end) {
+    Stage<BITS, G, NH> st;
+    fetch_cache_tile<BITS, G, NH>(st, rp, a.pool.Tcap, c_begin, u);
+    store_cache_tile<BITS, G, NH>(st, rp.lds + cur * kLdsTile, u);
+    for (int t = c_begin; t < c_end; ++t) {
+      __syncthreads();  // tile t is in lds[cur]; everybody is done reading lds[cur^1]
+      if (t + 1 < c_end && !dbg_skip_stage) fetch_cache_tile<BITS, G, NH>(st, rp, a.pool.Tcap, t + 1, u);
+      compute(cur, min(kTile, Tc - t * kTile));
+      if (t + 1 < c_end && !dbg_skip_stage) store_cache_tile<BITS, G, NH>(st, rp.lds + (cur ^ 1) * kLdsTile, u);
+      cur ^= 1;
     }
   }
-  {
-    const int f_begin = max(t_begin, n_ct) - n_ct, f_end = t_end - n_ct;
-    if (f_begin < f_end) {
-      FrameStage<NH> st;
-      fetch_frame_tile<NH>(st, xh, x_st, f_begin, n, u);
-      store_frame_tile<NH>(st, rp.lds[cur], is_v, u);  // lds[cur] was last read two barriers ago
-      for (int t = f_begin; t < f_end; ++t) {
-        __syncthreads();
-        if (t + 1 < f_end && !dbg_skip_stage) fetch_frame_tile<NH>(st, xh, x_st, t + 1, n, u);
-        compute(cur, min(kTile, n - t * kTile));
-        if (t + 1 < f_end && !dbg_skip_stage) store_frame_tile<NH>(st, rp.lds[cur ^ 1], is_v, u);
-        cur ^= 1;
-      }
+  if (f_begin < f_end) {
+    FrameStage<NH> st;
+    fetch_frame_tile<NH>(st, xh, x_st, is_v, f_begin, n, u);
+    store_frame_tile<NH>(st, rp.lds + cur * kLdsTile, is_v, u);  // lds[cur] was last read two barriers ago
+    for (int t = f_begin; t < f_end; ++t) {
+      __syncthreads();
+      if (t + 1 < f_end && !dbg_skip_stage) fetch_frame_tile<NH>(st, xh, x_st, is_v, t + 1, n, u);
+      compute(cur, min(kTile, n - t * kTile));
+      if (t + 1 < f_end && !dbg_skip_stage) store_frame_tile<NH>(st, rp.lds + (cur ^ 1) * kLdsTile, is_v, u);
+      cur ^= 1;
     }
   }
 
@@ -398,7 +428,7 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
   for (int cb = 0; cb < QB; ++cb) {
     const int q_row = q_row0 + 32 * cb + j;
     const float lsum = l[cb] + __shfl_xor(l[cb], 32);  // the two lane halves saw disjoint tokens
-    if (q_row >= n) continue;
+    if (q_row >= n || (a.variant & 32)) continue;
     if (S == 1) {
       const float inv = 1.0f / lsum;
       uint16_t* op = a.b.out[lb] + ((size_t)h * n + q_row) * kD;
@@ -422,9 +452,16 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
       if (hh == 0) *reinterpret_cast<float2*>(a.ws.attn_ml + row * 2) = make_float2(m[cb] * c2, lsum);
     }
   }
+
+  if (a.dbg) {
+    __syncthreads();
+    if (tid == 0) a.dbg[4 * id + 1] = wall_clock64();
+  }
 }
 
 // Merge of the key-range partials: out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
+// (A separate launch on purpose: a device-wide release/acquire inside the attention kernel costs an
+// L2 write-back per workgroup on this multi-die part, far more than a second small kernel.)
 __global__ __launch_bounds__(256) void combine_kernel(const AttendArgs a) {
   const int H = a.pool.H, n = a.n, S = a.n_splits;
   const size_t rows = (size_t)a.b.n_layers * H * n;
@@ -432,14 +469,21 @@ __global__ __launch_bounds__(256) void combine_kernel(const AttendArgs a) {
   const size_t row = gid >> 4;
   const int c = (int)(gid & 15) * 4;
   if (row >= rows) return;
+  float ms[16], ls[16];
   float M = kNegBig;
-  for (int s = 0; s < S; ++s) M = fmaxf(M, a.ws.attn_ml[(s * rows + row) * 2]);
-  float L = 0.f, acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
   for (int s = 0; s < S; ++s) {
     const float2 ml = *reinterpret_cast<const float2*>(a.ws.attn_ml + (s * rows + row) * 2);
-    const float w = __builtin_amdgcn_exp2f(ml.x - M);
+    ms[s] = ml.x;
+    ls[s] = ml.y;
+    M = fmaxf(M, ml.x);
+  }
+  float L = 0.f, acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+  for (int s = 0; s < S; ++s) {
+    const float w = __builtin_amdgcn_exp2f(ms[s] - M);
     const float4 o = *reinterpret_cast<const float4*>(a.ws.attn_o + (s * rows + row) * kD + c);
-    L += w * ml.y;
+    L += w * ls[s];
     acc[0] += w * o.x; acc[1] += w * o.y; acc[2] += w * o.z; acc[3] += w * o.w;
   }
   const float inv = 1.0f / L;
@@ -449,12 +493,12 @@ __global__ __launch_bounds__(256) void combine_kernel(const AttendArgs a) {
       make_uint2(pack_bf16(acc[0] * inv, acc[1] * inv), pack_bf16(acc[2] * inv, acc[3] * inv));
 }
 
-template <int BITS, int G, int NW, int QB>
+template <int BITS, int G, int NW, int QB, int DBG = 0>
 static hipError_t launch_attend_t(const AttendArgs& a, hipStream_t stream) {
   const int nqb = (a.n + 32 * QB * NW - 1) / (32 * QB * NW);
   const int n_groups = a.b.n_layers * a.pool.H * a.n_splits;
   const int grid = ((n_groups + 7) / 8) * 8 * nqb;
-  hipLaunchKernelGGL((attend_kernel<BITS, G, NW, QB>), dim3(grid), dim3(NW * 64), 0, stream, a);
+  hipLaunchKernelGGL((attend_kernel<BITS, G, NW, QB, DBG>), dim3(grid), dim3(NW * 64), 0, stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (a.n_splits > 1) {
@@ -469,12 +513,16 @@ template <int BITS, int G>
 static hipError_t launch_attend_v(const AttendArgs& a, hipStream_t stream) {
   switch (a.variant & 7) {
     case 1: return launch_attend_t<BITS, G, 4, 1>(a, stream);
+    case 3: return launch_attend_t<BITS, G, 8, 2>(a, stream);
+    case 5: if constexpr (BITS == 4 && G == 64) return launch_attend_t<BITS, G, 4, 2, 1>(a, stream); else return hipErrorInvalidValue;
+    case 6: if constexpr (BITS == 4 && G == 64) return launch_attend_t<BITS, G, 4, 2, 2>(a, stream); else return hipErrorInvalidValue;
+    case 7: if constexpr (BITS == 4 && G == 64) return launch_attend_t<BITS, G, 4, 2, 3>(a, stream); else return hipErrorInvalidValue;
     case 2: return launch_attend_t<BITS, G, 8, 1>(a, stream);
     default: return launch_attend_t<BITS, G, 4, 2>(a, stream);
   }
 }
 
-int attend_rows_per_workgroup(int variant) { return (variant & 7) == 1 ? 128 : 256; }
+int attend_rows_per_workgroup(int variant) { return (variant & 7) == 1 ? 128 : ((variant & 7) == 3 ? 512 : 256); }
 
 hipError_t launch_attend(const AttendArgs& a, hipStream_t stream) {
   const int bits = a.pool.bits, G = a.pool.G;

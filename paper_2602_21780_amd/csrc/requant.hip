@@ -53,7 +53,6 @@ __global__ __launch_bounds__(256) void requant_kernel(const RequantArgs a) {
   constexpr int kKGroups = kTile / G;  // key groups per block of 64 tokens (1 or 2)
   constexpr int kVGroups = kD / G;     // value groups per token (1 or 2)
 
-  __shared__ int src_row[kTile];
   __shared__ float xk[kTile][kD + 1];
   __shared__ float red_lo[4][kD], red_hi[4][kD];
   __shared__ float gs[2][kD], gz[2][kD];
@@ -69,9 +68,7 @@ __global__ __launch_bounds__(256) void requant_kernel(const RequantArgs a) {
   const int32_t* keep = a.ws.keep + (size_t)layer * a.ws.scores_stride;
   const int nv = min(kTile, Tn - u * kTile);  // valid new positions in this block
 
-  if (tid < kTile) src_row[tid] = tid < nv ? keep[u * kTile + tid] : -1;
-  __syncthreads();
-  const int s_row = src_row[r];
+  const int s_row = r < nv ? keep[u * kTile + r] : -1;
   const bool row_valid = s_row >= 0;
   const bool from_cache = row_valid && s_row < Tc;
 
@@ -80,6 +77,35 @@ __global__ __launch_bounds__(256) void requant_kernel(const RequantArgs a) {
     const int pos = u * kTile + r;
     dst.tok_frame[pos] = from_cache ? src.tok_frame[s_row] : a.frame_id;
     dst.tok_index[pos] = from_cache ? src.tok_index[s_row] : s_row - Tc;
+  }
+
+  // values: all loads are issued here, ahead of the key phase, so that the kernel pays one memory
+  // round trip for both; vraw = 16 gathered dwords (cache) or the 8 dwords of the frame row
+  uint32_t vraw[16];
+  float v_ps = 0.f, v_pz = 0.f;
+  int v_shift = 0;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) vraw[e] = 0u;
+  if (from_cache) {
+    const int blk = s_row / kTile, col = s_row % kTile;
+    if constexpr (kQuant) {
+      const uint32_t* rows = reinterpret_cast<const uint32_t*>(src.vc) + ((size_t)h * Tcap + (size_t)blk * kTile) * kRowDw + col / kPer;
+      v_shift = (col % kPer) * BITS;
+      const int vg = (cq * 16) / G;
+      v_ps = src.vs[((size_t)h * Tcap + s_row) * kVGroups + vg];
+      v_pz = src.vz[((size_t)h * Tcap + s_row) * kVGroups + vg];
+#pragma unroll
+      for (int e = 0; e < 16; ++e) vraw[e] = rows[(size_t)(cq * 16 + e) * kRowDw];
+    } else {
+      const uint16_t* rows = reinterpret_cast<const uint16_t*>(src.vc) + ((size_t)h * Tcap + (size_t)blk * kTile) * kD + col;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) vraw[e] = rows[(size_t)(cq * 16 + e) * kD];
+    }
+  } else if (row_valid) {
+    const uint4* p = reinterpret_cast<const uint4*>(a.b.v[lb] + (size_t)h * a.b.v_sh + (size_t)(s_row - Tc) * a.b.v_st + cq * 16);
+    const uint4 v0 = p[0], v1 = p[1];
+    vraw[0] = v0.x; vraw[1] = v0.y; vraw[2] = v0.z; vraw[3] = v0.w;
+    vraw[4] = v1.x; vraw[5] = v1.y; vraw[6] = v1.z; vraw[7] = v1.w;
   }
 
   // ---------------- keys ----------------
@@ -175,29 +201,19 @@ __global__ __launch_bounds__(256) void requant_kernel(const RequantArgs a) {
 #pragma unroll
   for (int e = 0; e < 16; ++e) x[e] = 0.f;
   if (from_cache) {
-    const int blk = s_row / kTile, col = s_row % kTile;
     if constexpr (kQuant) {
-      const uint32_t* rows = reinterpret_cast<const uint32_t*>(src.vc) + ((size_t)h * Tcap + (size_t)blk * kTile) * kRowDw + col / kPer;
-      const int shift = (col % kPer) * BITS;
-      const int vg = (cq * 16) / G;
-      const float vs = src.vs[((size_t)h * Tcap + s_row) * kVGroups + vg];
-      const float vz = src.vz[((size_t)h * Tcap + s_row) * kVGroups + vg];
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const uint32_t code = (rows[(size_t)(cq * 16 + e) * kRowDw] >> shift) & kMask;
-        x[e] = round_bf16(((float)code - vz) * vs);
+        const uint32_t code = (vraw[e] >> v_shift) & kMask;
+        x[e] = round_bf16(((float)code - v_pz) * v_ps);
       }
     } else {
-      const uint16_t* rows = reinterpret_cast<const uint16_t*>(src.vc) + ((size_t)h * Tcap + (size_t)blk * kTile) * kD + col;
 #pragma unroll
-      for (int e = 0; e < 16; ++e) x[e] = __uint_as_float((uint32_t)rows[(size_t)(cq * 16 + e) * kD] << 16);
+      for (int e = 0; e < 16; ++e) x[e] = __uint_as_float(vraw[e] << 16);
     }
   } else if (row_valid) {
-    const uint4* p = reinterpret_cast<const uint4*>(a.b.v[lb] + (size_t)h * a.b.v_sh + (size_t)(s_row - Tc) * a.b.v_st + cq * 16);
-    const uint4 v0 = p[0], v1 = p[1];
-    const uint32_t ww[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
 #pragma unroll
-    for (int e = 0; e < 8; ++e) { x[2 * e] = bf16_lo(ww[e]); x[2 * e + 1] = bf16_hi(ww[e]); }
+    for (int e = 0; e < 8; ++e) { x[2 * e] = bf16_lo(vraw[e]); x[2 * e + 1] = bf16_hi(vraw[e]); }
   }
 
   if constexpr (kQuant) {

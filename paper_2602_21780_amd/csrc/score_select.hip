@@ -3,15 +3,16 @@
 // The importance  S_j = (1/N_pooled) sum_i (Qbar Kbar^T)[i][j]  is linear in the pooled queries, so
 // it is evaluated as  S_j = qtilde . Kbar_j  with  qtilde = (1/N_pooled) sum_i Qbar_i :
 //   pool_query_kernel   one pass over Q: weighted row sums (weight 1/(H N_pooled) for a special
-//                       row, 1/(H N_pooled |group|) for a patch row) per workgroup; the partials are
-//                       folded in a fixed order by every score workgroup, so the result is
-//                       reproducible bit for bit and needs no atomics.
+//                       row, 1/(H N_pooled |group|) for a patch row), one workgroup and one
+//                       partial per head; every score workgroup adds the H partials in head order,
+//                       so the result is reproducible bit for bit and needs no atomics.
 //   score_kernel        one pass over the packed keys of the prunable middle: dequantized view,
-//                       head mean, dot product with qtilde.  HBM-bound: 64 tokens x all heads per
-//                       workgroup, 16 channels per thread, coalesced 8-byte code loads.
-//   select_kernel       exact top-k by radix select on order-preserving integer keys (4 passes of
-//                       8 bits, histograms in LDS), ties at the threshold resolved toward smaller
-//                       positions, then an ordered compaction that emits the keep list ascending.
+//                       head mean, dot product with qtilde.  64 tokens x all heads per workgroup,
+//                       16 channels per thread, all loads of a workgroup issued before any use.
+//   select_kernel       exact top-k by radix select on order-preserving integer keys held in
+//                       registers (4 passes of 8 bits, histograms in LDS, bin search by a shuffle
+//                       scan), ties at the threshold resolved toward smaller positions, then an
+//                       ordered compaction that emits the keep list ascending.
 // Compiled with -ffp-contract=off: the dequantized view must be (code - zero) * scale with one
 // rounding per operation.
 #include "xsv_internal.h"
@@ -22,19 +23,21 @@ __device__ __forceinline__ float round_bf16(float x) { return (float)(__bf16)x; 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
-constexpr int kPoolRows = 128;  // query rows per workgroup of pool_query_kernel
+constexpr int kPoolThreads = 1024;
 
-// grid (chunks, H, layers), 256 threads: thread = (row lane tid/8 of 32, channel run tid%8)
-__global__ __launch_bounds__(256) void pool_query_kernel(const ScoreArgs a) {
-  __shared__ float red[32][kD + 1];
-  const int lb = blockIdx.z, h = blockIdx.y, chunk = blockIdx.x;
+// grid (H, layers), 1024 threads: thread = (row lane tid/8 of 128, channel run tid%8).  One partial
+// weighted row sum [64] per head; the score kernel adds the H partials in head order.
+__global__ __launch_bounds__(kPoolThreads) void pool_query_kernel(const ScoreArgs a) {
+  __shared__ float red[kPoolThreads / 8][kD + 1];
+  const int lb = blockIdx.y, h = blockIdx.x;
   const int H = a.pool.H, n = a.n, n_s = a.n_special, g = a.pool_size;
   const int n_pooled = n_s + (n - n_s + g - 1) / g;
   const int tid = threadIdx.x, rl = tid >> 3, o = tid & 7;
   const uint16_t* qh = a.b.q[lb] + (size_t)h * a.b.q_sh;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   const float base = (float)(H * n_pooled);
-  for (int r = chunk * kPoolRows + rl; r < min(n, (chunk + 1) * kPoolRows); r += 32) {
+#pragma unroll 4
+  for (int r = rl; r < n; r += kPoolThreads / 8) {
     float w;
     if (r < n_s) {
       w = 1.0f / base;
@@ -54,95 +57,111 @@ __global__ __launch_bounds__(256) void pool_query_kernel(const ScoreArgs a) {
 #pragma unroll
   for (int e = 0; e < 8; ++e) red[rl][o * 8 + e] = acc[e];
   __syncthreads();
-  float* part = a.ws.qpart + (size_t)(a.b.layer0 + lb) * a.ws.qpart_rows * kD;
-  if (tid < kD) {
+  // fold the 128 row lanes in a fixed order: 4 segments of 32, then a chain
+  __shared__ float seg[4][kD];
+  if (tid < 4 * kD) {
+    const int sg = tid >> 6, c = tid & 63;
     float s = 0.f;
-    for (int i = 0; i < 32; ++i) s += red[i][tid];
-    part[(size_t)(h * gridDim.x + chunk) * kD + tid] = s;
+    for (int i = sg * 32; i < sg * 32 + 32; ++i) s += red[i][c];
+    seg[sg][c] = s;
+  }
+  __syncthreads();
+  if (tid < kD) {
+    float* part = a.ws.qpart + (size_t)(a.b.layer0 + lb) * a.ws.qpart_rows * kD;
+    part[(size_t)h * kD + tid] = ((seg[0][tid] + seg[1][tid]) + seg[2][tid]) + seg[3][tid];
   }
 }
 
 hipError_t launch_pool_query(const ScoreArgs& a, hipStream_t stream) {
-  const int chunks = (a.n + kPoolRows - 1) / kPoolRows;
-  hipLaunchKernelGGL(pool_query_kernel, dim3(chunks, a.pool.H, a.b.n_layers), dim3(256), 0, stream, a);
+  hipLaunchKernelGGL(pool_query_kernel, dim3(a.pool.H, a.b.n_layers), dim3(kPoolThreads), 0, stream, a);
   return hipGetLastError();
 }
 
 // grid (blocks of 64 cache positions covering the middle, layers), 256 threads:
-// thread = (token tid/4 of the block, channel quarter tid%4 = 16 channels)
-template <int BITS, int G>
+// thread = (token tid/4 of the block, channel quarter tid%4 = 16 channels).
+// Everything a workgroup needs is requested up front (one memory round trip): the H partial query
+// sums, the group parameters of all heads (staged in LDS, they are shared by the block's tokens)
+// and the thread's packed codes of all heads.
+template <int BITS, int G, int HMAX>
 __global__ __launch_bounds__(256) void score_kernel(const ScoreArgs a) {
+  constexpr bool kQuant = BITS != 16;
+  constexpr int kGroups = kQuant ? kTile / G : 1;  // key groups inside a block of 64 positions
+  constexpr int kRowDw = kD * BITS / 32;           // dwords per key row
+  constexpr int kDwT = kRowDw / 4;                 // dwords per thread (16 channels)
+  __shared__ float qtilde[kD];
+  __shared__ float prm[kQuant ? HMAX * kGroups * 2 * kD : 1];  // [head][group][scale|zero][channel]
+
   const int lb = blockIdx.y;
   const int H = a.pool.H;
   const int tid = threadIdx.x, r = tid >> 2, cq = tid & 3;
-  const int first_block = a.T_first / kTile;
-  const int pos = (first_block + blockIdx.x) * kTile + r;  // cache position
+  const int block = a.T_first / kTile + blockIdx.x;
+  const int pos = block * kTile + r;  // cache position
   const bool valid = pos >= a.T_first && pos < a.T_first + a.P;
+  const bool plain = a.k_plain != nullptr;
 
-  // qtilde: fold the per-workgroup partial query sums in a fixed order (4 segments, then a chain)
-  __shared__ float seg[4][kD];
-  __shared__ float qtilde[kD];
-  {
-    const int n_parts = ((a.n + kPoolRows - 1) / kPoolRows) * H;
-    const float* part = a.ws.qpart + (size_t)(a.b.layer0 + lb) * a.ws.qpart_rows * kD;
-    const int per = (n_parts + 3) / 4, sg = tid >> 6, c = tid & 63;
-    float s = 0.f;
-    for (int i = sg * per; i < min(n_parts, (sg + 1) * per); ++i) s += part[(size_t)i * kD + c];
-    seg[sg][c] = s;
-    __syncthreads();
-    if (tid < kD) qtilde[tid] = ((seg[0][tid] + seg[1][tid]) + seg[2][tid]) + seg[3][tid];
-    __syncthreads();
+  const uint32_t* src;
+  size_t head_stride;  // dwords
+  if (plain) {
+    src = reinterpret_cast<const uint32_t*>(a.k_plain) + (size_t)(pos - a.T_first) * kRowDw + cq * kDwT;
+    head_stride = (size_t)a.P * kRowDw;
+  } else {
+    const LayerCache lc = layer_cache(a.pool, a.b.src_buf(lb), a.b.layer0 + lb);
+    src = reinterpret_cast<const uint32_t*>(lc.kc) + (size_t)pos * kRowDw + cq * kDwT;
+    head_stride = (size_t)a.pool.Tcap * kRowDw;
   }
-  const float* qt = qtilde + cq * 16;
+  if (tid < kD) {  // the H partial sums, in head order
+    const float* part = a.ws.qpart + (size_t)(a.b.layer0 + lb) * a.ws.qpart_rows * kD;
+    float s = 0.f;
+#pragma unroll 16
+    for (int h = 0; h < H; ++h) s += part[(size_t)h * kD + tid];
+    qtilde[tid] = s;
+  }
 
   float acc[16];
 #pragma unroll
   for (int e = 0; e < 16; ++e) acc[e] = 0.f;
-
-  if (valid) {
-    if (a.k_plain != nullptr || BITS == 16) {
-      // bf16 rows: the plain tensor [H][P][64] of the stateless form, or the bf16 cache
-      const uint16_t* base;
-      size_t head_stride;
-      if (a.k_plain != nullptr) {
-        base = a.k_plain + (size_t)(pos - a.T_first) * kD;
-        head_stride = (size_t)a.P * kD;
-      } else {
-        const LayerCache lc = layer_cache(a.pool, a.b.src_buf(lb), a.b.layer0 + lb);
-        base = reinterpret_cast<const uint16_t*>(lc.kc) + (size_t)pos * kD;
-        head_stride = (size_t)a.pool.Tcap * kD;
-      }
-      for (int h = 0; h < H; ++h) {
-        const uint4* p = reinterpret_cast<const uint4*>(base + h * head_stride + cq * 16);
-        const uint4 v0 = p[0], v1 = p[1];
-        const uint32_t ww[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+  for (int h0 = 0; h0 < H; h0 += HMAX) {  // heads in chunks of HMAX (one chunk for H <= HMAX)
+    const int hn = min(HMAX, H - h0);
+    // codes (or bf16 rows) of this thread's 16 channels, all heads of the chunk
+    uint32_t w[HMAX][kDwT];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          acc[2 * e] += bf16_lo(ww[e]);
-          acc[2 * e + 1] += bf16_hi(ww[e]);
-        }
-      }
-    } else {
+    for (int h = 0; h < HMAX; ++h)
+#pragma unroll
+      for (int i = 0; i < kDwT; ++i) w[h][i] = (valid && h < hn) ? src[(h0 + h) * head_stride + i] : 0u;
+    if constexpr (kQuant) {
       const LayerCache lc = layer_cache(a.pool, a.b.src_buf(lb), a.b.layer0 + lb);
-      constexpr int kRowDw = kD * BITS / 32;   // dwords per key row
-      constexpr int kDwPerThread = kRowDw / 4;  // 16 channels
-      constexpr uint32_t mask = (1u << BITS) - 1u;
       const int gcap = a.pool.Tcap / G;
-      for (int h = 0; h < H; ++h) {
-        const uint32_t* codes = reinterpret_cast<const uint32_t*>(lc.kc) + ((size_t)h * a.pool.Tcap + pos) * kRowDw + cq * kDwPerThread;
-        const float* ks = lc.ks + ((size_t)h * gcap + pos / G) * kD + cq * 16;
-        const float* kz = lc.kz + ((size_t)h * gcap + pos / G) * kD + cq * 16;
-        uint32_t w[kDwPerThread];
+      if (h0 > 0) __syncthreads();  // the previous chunk's parameters are no longer read
+      for (int i = tid; i < hn * kGroups * 2 * kD; i += 256) {
+        const int c = i % kD, sz = (i / kD) & 1, gi = (i / (2 * kD)) % kGroups, h = i / (2 * kD * kGroups);
+        const float* p = sz ? lc.kz : lc.ks;
+        prm[i] = p[((size_t)(h0 + h) * gcap + block * kGroups + gi) * kD + c];
+      }
+    }
+    __syncthreads();
 #pragma unroll
-        for (int i = 0; i < kDwPerThread; ++i) w[i] = codes[i];
+    for (int h = 0; h < HMAX; ++h) {
+      if (h < hn) {
+        if constexpr (kQuant) {
+          constexpr uint32_t mask = (1u << (BITS & 15)) - 1u;
+          const float* ks = prm + ((h * kGroups + (r / G) % kGroups) * 2) * kD + cq * 16;
+          const float* kz = ks + kD;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const uint32_t code = (w[(e * BITS) / 32] >> ((e * BITS) % 32)) & mask;
-          acc[e] += round_bf16(((float)code - kz[e]) * ks[e]);
+          for (int e = 0; e < 16; ++e) {
+            const uint32_t code = (w[h][(e * BITS) / 32] >> ((e * BITS) % 32)) & mask;
+            acc[e] += round_bf16(((float)code - kz[e]) * ks[e]);
+          }
+        } else {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            acc[2 * e] += bf16_lo(w[h][e]);
+            acc[2 * e + 1] += bf16_hi(w[h][e]);
+          }
         }
       }
     }
   }
+  const float* qt = qtilde + cq * 16;
   float dot = 0.f;
   const float fH = (float)H;
 #pragma unroll
@@ -157,11 +176,11 @@ hipError_t launch_score(const ScoreArgs& a, hipStream_t stream) {
   const int last_block = (a.T_first + a.P - 1) / kTile;
   const dim3 grid(last_block - first_block + 1, a.b.n_layers);
   const int bits = a.k_plain ? 16 : a.pool.bits, G = a.pool.G;
-  if (bits == 16) hipLaunchKernelGGL((score_kernel<16, 64>), grid, dim3(256), 0, stream, a);
-  else if (bits == 4 && G == 64) hipLaunchKernelGGL((score_kernel<4, 64>), grid, dim3(256), 0, stream, a);
-  else if (bits == 4 && G == 32) hipLaunchKernelGGL((score_kernel<4, 32>), grid, dim3(256), 0, stream, a);
-  else if (bits == 2 && G == 64) hipLaunchKernelGGL((score_kernel<2, 64>), grid, dim3(256), 0, stream, a);
-  else if (bits == 2 && G == 32) hipLaunchKernelGGL((score_kernel<2, 32>), grid, dim3(256), 0, stream, a);
+  if (bits == 16) hipLaunchKernelGGL((score_kernel<16, 64, 16>), grid, dim3(256), 0, stream, a);
+  else if (bits == 4 && G == 64) hipLaunchKernelGGL((score_kernel<4, 64, 16>), grid, dim3(256), 0, stream, a);
+  else if (bits == 4 && G == 32) hipLaunchKernelGGL((score_kernel<4, 32, 16>), grid, dim3(256), 0, stream, a);
+  else if (bits == 2 && G == 64) hipLaunchKernelGGL((score_kernel<2, 64, 16>), grid, dim3(256), 0, stream, a);
+  else if (bits == 2 && G == 32) hipLaunchKernelGGL((score_kernel<2, 32, 16>), grid, dim3(256), 0, stream, a);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }
@@ -175,10 +194,11 @@ __device__ __forceinline__ uint32_t order_key(float f) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-constexpr int kSelThreads = 1024;
+constexpr int kSelThreads = 256;  // 4 waves: cheap barriers; one histogram bin per thread
 
 // exclusive prefix sums of two counters over the workgroup's threads, in thread order
 __device__ __forceinline__ void block_exclusive_scan2(int& a, int& b, int* sh /* 2*16 */, int& total_a, int& total_b) {
+  static_assert(kSelThreads / 64 <= 16, "wave totals live in 16 slots");
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int ia = a, ib = b;
 #pragma unroll
@@ -199,53 +219,80 @@ __device__ __forceinline__ void block_exclusive_scan2(int& a, int& b, int* sh /*
   __syncthreads();
 }
 
-// one workgroup per layer
+// one workgroup per layer; KPT > 0: each thread keeps its (at most KPT) keys in registers
+template <int KPT>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectArgs a) {
   __shared__ int hist[256];
+  __shared__ int wave_tot[4];
   __shared__ int sh_scan[32];
   __shared__ uint32_t sh_prefix;
   __shared__ int sh_need;
-  const int tid = threadIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const float* scores = a.scores + (size_t)blockIdx.x * a.scores_stride;
   int32_t* keep = a.keep + (size_t)blockIdx.x * a.keep_stride;
   const int P = a.P, k = a.k;
 
+  // thread t owns the contiguous positions [t*per, (t+1)*per)
+  const int per = (P + kSelThreads - 1) / kSelThreads;
+  const int j0 = min(P, tid * per), j1 = min(P, j0 + per);
+  uint32_t keys[KPT > 0 ? KPT : 1];
+  if constexpr (KPT > 0) {
+#pragma unroll
+    for (int i = 0; i < KPT; ++i) keys[i] = (j0 + i < j1) ? order_key(scores[j0 + i]) : 0u;
+  }
+  auto key_at = [&](int i) -> uint32_t {  // i-th key of this thread
+    if constexpr (KPT > 0) return keys[i];
+    else return order_key(scores[j0 + i]);
+  };
+
   // k-th largest key by radix select, most significant byte first
   uint32_t prefix = 0;
   int need = k;  // rank still to find inside the current prefix class (1-based from the top)
+#pragma unroll
   for (int pass = 0; pass < 4; ++pass) {
     const int shift = 24 - 8 * pass;
-    if (tid < 256) hist[tid] = 0;
+    hist[tid] = 0;
     __syncthreads();
     const uint32_t hi_mask = pass == 0 ? 0u : (0xffffffffu << (shift + 8));
-    for (int j = tid; j < P; j += kSelThreads) {
-      const uint32_t key = order_key(scores[j]);
-      if ((key & hi_mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
+    if constexpr (KPT > 0) {
+#pragma unroll
+      for (int i = 0; i < KPT; ++i)
+        if (j0 + i < j1 && (keys[i] & hi_mask) == prefix) atomicAdd(&hist[(keys[i] >> shift) & 255u], 1);
+    } else {
+      for (int i = 0; i < j1 - j0; ++i) {
+        const uint32_t key = key_at(i);
+        if ((key & hi_mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
+      }
     }
     __syncthreads();
-    if (tid == 0) {
-      int cum = 0, bin = 255;
-      for (; bin > 0; --bin) {
-        if (cum + hist[bin] >= need) break;
-        cum += hist[bin];
-      }
-      sh_prefix = prefix | ((uint32_t)bin << shift);
-      sh_need = need - cum;
+    // bin b holds the wanted rank iff  (#keys in bins above b) < need <= (that + hist[b]);
+    // suffix sums over the 256 bins: per-wave shuffle scan + 4 wave totals
+    const int h = hist[tid];
+    int incl = h;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const int v = __shfl_down(incl, d);
+      if (lane + d < 64) incl += v;
+    }
+    if (lane == 0) wave_tot[wave] = incl;
+    __syncthreads();
+    int above = incl - h;
+    for (int w = wave + 1; w < 4; ++w) above += wave_tot[w];
+    if (above < need && need <= above + h) {
+      sh_prefix = prefix | ((uint32_t)tid << shift);
+      sh_need = need - above;
     }
     __syncthreads();
     prefix = sh_prefix;
     need = sh_need;
-    __syncthreads();
   }
   const uint32_t thr = prefix;  // key of the k-th largest score
   const int need_eq = need;     // how many of the scores equal to it are kept (smallest positions)
 
-  // ordered compaction: thread t owns the contiguous positions [t*per, (t+1)*per)
-  const int per = (P + kSelThreads - 1) / kSelThreads;
-  const int j0 = min(P, tid * per), j1 = min(P, j0 + per);
+  // ordered compaction
   int n_gt = 0, n_eq = 0;
-  for (int j = j0; j < j1; ++j) {
-    const uint32_t key = order_key(scores[j]);
+  for (int i = 0; i < j1 - j0; ++i) {
+    const uint32_t key = key_at(i);
     n_gt += key > thr;
     n_eq += key == thr;
   }
@@ -253,21 +300,24 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectArgs a)
   block_exclusive_scan2(gt_before, eq_before, sh_scan, tot_gt, tot_eq);
   int out = a.T_first + gt_before + min(eq_before, need_eq);
   int eq_rank = eq_before;
-  for (int j = j0; j < j1; ++j) {
-    const uint32_t key = order_key(scores[j]);
+  for (int i = 0; i < j1 - j0; ++i) {
+    const uint32_t key = key_at(i);
     bool take = key > thr;
     if (key == thr) {
       take = eq_rank < need_eq;
       ++eq_rank;
     }
-    if (take) keep[out++] = a.T_first + j;
+    if (take) keep[out++] = a.T_first + j0 + i;
   }
   for (int i = tid; i < a.T_first; i += kSelThreads) keep[i] = i;
   for (int i = tid; i < a.T_cur; i += kSelThreads) keep[a.T_first + k + i] = a.T_first + P + i;
 }
 
 hipError_t launch_select(const SelectArgs& a, hipStream_t stream) {
-  hipLaunchKernelGGL(select_kernel, dim3(a.n_layers), dim3(kSelThreads), 0, stream, a);
+  static_assert(kSelThreads == 256, "one histogram bin per thread");
+  if (a.P <= 16 * kSelThreads) hipLaunchKernelGGL(select_kernel<16>, dim3(a.n_layers), dim3(kSelThreads), 0, stream, a);
+  else if (a.P <= 32 * kSelThreads) hipLaunchKernelGGL(select_kernel<32>, dim3(a.n_layers), dim3(kSelThreads), 0, stream, a);
+  else hipLaunchKernelGGL(select_kernel<0>, dim3(a.n_layers), dim3(kSelThreads), 0, stream, a);
   return hipGetLastError();
 }
 

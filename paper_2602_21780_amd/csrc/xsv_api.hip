@@ -45,7 +45,8 @@ struct xsv_ctx {
   std::vector<LayerState> layers;
   std::vector<void*> allocs;
   int splits_single = 0, splits_batched = 0;
-  int attend_variant = 0;
+  int attend_variant = 3;  // 8 waves x 64 query rows per workgroup
+  unsigned long long* dbg = nullptr;
   int max_splits = 1;
   size_t part_rows = 0;  // rows the partial-output workspace holds
   int n_cu = 256;
@@ -127,7 +128,7 @@ int choose_splits(const xsv_ctx* ctx, int n_layers, int Tc, int requested) {
     const int wgs = ((c.tokens_per_frame + rows - 1) / rows) * c.n_heads * n_layers;
     // fill the workgroup slots of the chip (2 per compute unit; 1 for the 8-wave variant) in ONE
     // round, never with ranges shorter than 4 tiles
-    const int slots = ((ctx->attend_variant & 7) == 2 ? 1 : 2) * ctx->n_cu;
+    const int slots = ((ctx->attend_variant & 7) >= 2 && (ctx->attend_variant & 7) <= 3 ? 1 : 2) * ctx->n_cu;
     s = std::max(1, slots / wgs);
     s = std::min(s, std::max(1, n_tiles / 4));
   }
@@ -177,6 +178,7 @@ int do_attend(xsv_ctx* ctx, int layer0, int n_layers, const xsv_tensor* q, const
   a.Tc = ctx->layers[layer0].T;
   a.n = ctx->cfg.tokens_per_frame;
   a.variant = ctx->attend_variant;
+  a.dbg = ctx->dbg;
   a.n_splits = choose_splits(ctx, n_layers, a.Tc, splits_req);
   a.qscale = ctx->cfg.softmax_scale * 1.4426950408889634f;
   if (launch_attend(a, ctx->stream) != hipSuccess) return hip_fail(ctx);
@@ -353,7 +355,7 @@ int xsv_create(const xsv_config* cfg, void* hip_stream, xsv_ctx** out) {
   Workspace& w = ctx->ws;
   std::memset(&w, 0, sizeof(w));
   w.scores_stride = p.Tcap + (int)n;
-  w.qpart_rows = (int)((n + 127) / 128) * c.n_heads;
+  w.qpart_rows = c.n_heads;
   A(&w.scores, (size_t)c.n_layers * w.scores_stride, true);
   A(&w.keep, (size_t)c.n_layers * w.scores_stride, true);
   A(&w.qpart, (size_t)c.n_layers * w.qpart_rows * kD, true);
@@ -396,8 +398,20 @@ int xsv_set_attend_splits(xsv_ctx* ctx, int per_layer_calls, int batched_calls) 
   return XSV_OK;
 }
 
+// debugging aid: per-workgroup timestamps of the last attention launch (host buffer of 4*max_wgs u64)
+int xsv_debug_times(xsv_ctx* ctx, unsigned long long* host, int max_wgs) {
+  if (!ctx) return XSV_ERR_ARG;
+  if (!ctx->dbg) {
+    if (dev_alloc(ctx, &ctx->dbg, (size_t)4 * 16384, true) != XSV_OK) return XSV_ERR_OOM;
+    return XSV_OK;
+  }
+  if (hipStreamSynchronize(ctx->stream) != hipSuccess) return XSV_ERR_HIP;
+  if (host && hipMemcpy(host, ctx->dbg, (size_t)4 * std::min(max_wgs, 16384) * 8, hipMemcpyDeviceToHost) != hipSuccess) return XSV_ERR_HIP;
+  return XSV_OK;
+}
+
 int xsv_set_attend_variant(xsv_ctx* ctx, int variant) {
-  if (!ctx || variant < 0 || variant > 31) return XSV_ERR_ARG;
+  if (!ctx || variant < 0 || variant > 63) return XSV_ERR_ARG;
   ctx->attend_variant = variant;
   return XSV_OK;
 }
@@ -671,7 +685,7 @@ int xsv_score(void* hip_stream, xsv_tensor q, const void* k_mid_bf16, int H, int
   s.b.n_layers = 1; s.b.layer0 = 0;
   s.b.q[0] = static_cast<const uint16_t*>(q.ptr);
   s.b.q_sh = q.stride_head; s.b.q_st = q.stride_token;
-  s.ws.qpart_rows = ((n + 127) / 128) * H;
+  s.ws.qpart_rows = H;
   s.ws.qpart = tmp.get<float>((size_t)s.ws.qpart_rows * kD);
   if (!s.ws.qpart) return XSV_ERR_OOM;
   s.ws.scores = scores;
