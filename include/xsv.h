@@ -119,8 +119,8 @@ int xsv_set_attend_splits(xsv_ctx* ctx, int per_layer_calls, int batched_calls);
 /* Tuning: 0 = xsv_step / xsv_step_all_layers run everything on the context's stream, in order;
  * 1 (default) = the score/select/re-quantize chain overlaps the attention kernel. */
 int xsv_set_overlap(xsv_ctx* ctx, int enabled);
-/* Tuning: workgroup shape of the attention kernel.  3 (default) = 8 waves x 64 query rows,
- * 0 = 4 waves x 64 rows, 1 = 4 waves x 32 rows, 2 = 8 waves x 32 rows.  Results agree to rounding. */
+/* Tuning: workgroup shape of the attention kernel (waves x query rows per wave).  3 (default) = 8 x 64,
+ * 0 = 4 x 64, 1 = 4 x 32, 2 = 8 x 32.  Other values: XSV_ERR_ARG.  Results agree to rounding. */
 int xsv_set_attend_variant(xsv_ctx* ctx, int variant);
 
 /* ---- introspection, synchronous, HOST buffers, canonical unpacked layout ------------------------ */

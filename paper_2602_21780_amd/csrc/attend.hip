@@ -19,6 +19,8 @@
 //   blockIdx is remapped so that all query blocks of one (layer, head, key range) land on the same
 //   XCD and share its L2.  With n_splits > 1 each key range writes unnormalized partials that
 //   combine_kernel merges.
+#include <type_traits>
+
 #include "xsv_internal.h"
 
 namespace xsv {
@@ -231,8 +233,25 @@ __device__ __forceinline__ void store_frame_tile(const FrameStage<NH>& st, uint1
   }
 }
 
+// max of a value with the one held by the lane 32 apart (the other half of the same query's
+// tokens): one v_permlane32_swap instead of a round trip through the LDS crossbar
+__device__ __forceinline__ float xhalf_max(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+// A callable that issues `N` MFMAs per call (the softmax block uses N to lay out its issue order).
+template <int N, typename F>
+struct MfmaHook {
+  static constexpr int kMfma = N;
+  F f;
+  __device__ __forceinline__ void operator()(int i) const { f(i); }
+};
+template <int N, typename F>
+__device__ __forceinline__ MfmaHook<N, F> with_mfma(F f) { return MfmaHook<N, F>{f}; }
+
 // ---- the kernel ----------------------------------------------------------------------------------
-template <int BITS, int G, int NW, int QB, int DBG = 0>
+template <int BITS, int G, int NW, int QB>
 __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
   constexpr int NT = NW * 64, NH = NT / 2;
   constexpr int kRowsWG = 32 * QB * NW;  // query rows per workgroup
@@ -254,11 +273,6 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int j = lane & 31, hh = lane >> 5;
-  if (a.dbg && tid == 0) {
-    a.dbg[4 * id] = wall_clock64();
-    a.dbg[4 * id + 2] = __builtin_amdgcn_s_getreg((4) | (0 << 6) | (31 << 11));
-    a.dbg[4 * id + 3] = __builtin_amdgcn_s_getreg((20) | (0 << 6) | (31 << 11));
-  }
 
   const LayerCache lc = layer_cache(a.pool, a.b.src_buf(lb), a.b.layer0 + lb);
   const uint16_t* qh = a.b.q[lb] + (size_t)h * a.b.q_sh;
@@ -311,102 +325,164 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
   }
   const int krow = tau(j);
 
-  // one tile of 64 tokens held in LDS buffer `buf`, of which the first `valid` are real.
-  // Order inside a half-step of 32 tokens (all independent work of a wave is interleaved so that
-  // the matrix pipe runs under the softmax arithmetic): logits of every query block, then per block
-  // softmax → its PV product; K fragments of the next half-step and the V fragments are requested
-  // from LDS before the softmax so they arrive while it runs.
-  const bool dbg_skip_compute = a.variant & 8, dbg_skip_stage = a.variant & 16;
-  auto compute = [&](int buf, int valid) {
-    if (n_cb == 0 || dbg_skip_compute) return;
-    const uint16_t* lk = lds_k[buf] + krow * kLdsStride + 8 * hh;
-    const uint16_t* lv = lds_v[buf] + j * kLdsStride + 8 * hh;
-    bf16x8 kf[4];
+  // softmax of one query block over the 32 tokens of a half-step: masks tokens >= valid, moves the
+  // (lazy) reference maximum, exponentiates into packed bf16 and adds the row sums.  `hook(i)`,
+  // i = 0..3, is called before each quarter of the exponentials: the caller issues MFMAs there, so
+  // that the matrix pipe works underneath this arithmetic.
+  auto softmax_half = [&](f32x16& sv, uint32_t (&pw)[8], float& mref, float& lsum, f32x16& oa, f32x16& ob, int tok0,
+                          int valid, auto&& hook) {
+    if (valid < tok0 + 32) {  // tokens past the end of the cache / of the frame
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) kf[ks] = *reinterpret_cast<const bf16x8*>(lk + 16 * ks);
+      for (int r = 0; r < 16; ++r)
+        if (tok0 + 16 * (r >> 3) + 8 * hh + (r & 7) >= valid) sv[r] = -INFINITY;
+    }
+    float mx = fmaxf(sv[0], sv[1]);
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-      if (32 * half >= valid) break;
-      f32x16 s[QB];
+    for (int r = 2; r < 16; r += 2) mx = fmaxf(mx, fmaxf(sv[r], sv[r + 1]));
+    mx = xhalf_max(mx);
+    // the reference maximum only moves when some row's maximum grows by more than 2^kLazyLog2;
+    // until then probabilities may exceed 1 (by at most that factor), which fp32 sums and
+    // bf16 products absorb, and the accumulators need no rescaling
+    if (__any((mx - mref) * c2 > kLazyLog2)) {
+      const float m_new = fmaxf(mref, mx);
+      const float alpha = __builtin_amdgcn_exp2f((mref - m_new) * c2);
+      lsum *= alpha;
 #pragma unroll
-      for (int cb = 0; cb < QB; ++cb) {
+      for (int r = 0; r < 16; ++r) { oa[r] *= alpha; ob[r] *= alpha; }
+      mref = m_new;
+    }
+    const float mc = -mref * c2;
+    float psum = lsum;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s[cb][r] = 0.f;
-        if (cb < n_cb) {
+    for (int q4 = 0; q4 < 4; ++q4) {
+      hook(q4);
 #pragma unroll
-          for (int ks = 0; ks < (DBG == 2 ? 1 : 4); ++ks) s[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[cb][ks], s[cb], 0, 0, 0);
+      for (int r = 4 * q4; r < 4 * q4 + 4; r += 2) {
+        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r], c2, mc));
+        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r + 1], c2, mc));
+        pw[r >> 1] = pack_bf16(p0, p1);
+        // row sum of the ROUNDED probabilities (what the PV product sees): v_dot2c_f32_bf16
+        psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pw[r >> 1]),
+                                               __builtin_bit_cast(bf16x2, 0x3f803f80u), psum, false);
+      }
+    }
+    // keep this block's probabilities in this block (the compiler would otherwise sink the
+    // exponentials down to their consumer, next to the MFMAs they are meant to overlap with)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) asm volatile("" : "+v"(pw[i]));
+    // prescribed issue order of this block, per quarter: its MFMAs spread between its 12 vector
+    // instructions (4 fma, 4 exp, 2 convert, 2 dot) — the MFMAs execute while the VALU works
+    constexpr int kMfmaPerQuarter = std::remove_reference_t<decltype(hook)>::kMfma;
+    if constexpr (kMfmaPerQuarter > 0) {
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        // masks: 0x008 MFMA, 0x002 VALU (without transcendentals), 0x400 transcendental
+        if constexpr (kMfmaPerQuarter == 2) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+          __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
+          __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+        } else {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+          __builtin_amdgcn_sched_group_barrier(0x400, 4, 0);
+          __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
         }
       }
-      bf16x8 vf[2][2];
+    }
+    lsum = psum;
+  };
+
+  // one tile of 64 tokens held in LDS buffer `buf`, of which the first `valid` are real
+  auto compute = [&](int buf, int valid) {
+    if (n_cb == 0) return;
+    const uint16_t* lk = lds_k[buf] + krow * kLdsStride + 8 * hh;
+    const uint16_t* lv = lds_v[buf] + j * kLdsStride + 8 * hh;
+    auto load_k = [&](bf16x8 (&kf)[4], int half) {
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) kf[ks] = *reinterpret_cast<const bf16x8*>(lk + 32 * half * kLdsStride + 16 * ks);
+    };
+    auto load_v = [&](bf16x8 (&vf)[2][2], int half) {
 #pragma unroll
       for (int k2 = 0; k2 < 2; ++k2) {
         vf[k2][0] = *reinterpret_cast<const bf16x8*>(lv + 32 * half + 16 * k2);
         vf[k2][1] = *reinterpret_cast<const bf16x8*>(lv + 32 * kLdsStride + 32 * half + 16 * k2);
       }
-      if (half == 0 && valid > 32) {
+    };
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    // step i (0..3) of S^T = K Q^T for one query block (contraction over 16 channels per step)
+    auto qk_step = [&](f32x16& sv, const bf16x8 (&kf)[4], int cb, int i) {
+      sv = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i], qf[cb][i], i == 0 ? zero : sv, 0, 0, 0);
+    };
+    // step i (0..3) of O^T += V^T P^T for one query block: token step i/2, channel half i%2
+    auto pv_step = [&](int cb, const bf16x8 (&vf)[2][2], const uint32_t (&pw)[8], int i) {
+      const int k2 = i >> 1;
+      const bf16x8 pb = __builtin_bit_cast(bf16x8, make_uint4(pw[4 * k2], pw[4 * k2 + 1], pw[4 * k2 + 2], pw[4 * k2 + 3]));
+      if (i & 1) o1[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[k2][1], pb, o1[cb], 0, 0, 0);
+      else o0[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[k2][0], pb, o0[cb], 0, 0, 0);
+    };
+
+    if constexpr (QB == 2) {
+      // Software pipeline over the two half-steps and the two query blocks A, B of the wave: every
+      // block of softmax arithmetic has independent MFMAs issued inside it —
+      //   SM(A,h):  S(B,h) [and O(B,h-1)]      SM(B,h):  O(A,h) [and S(A,h+1)]
+      // Blocks past the end of the frame are computed on clamped rows and never stored.
+      bf16x8 kf[4], vf[2][2];
+      f32x16 sA, sB;
+      uint32_t pA[8], pB[8];
+      load_k(kf, 0);
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) kf[ks] = *reinterpret_cast<const bf16x8*>(lk + 32 * kLdsStride + 16 * ks);
-      }
+      for (int i = 0; i < 4; ++i) qk_step(sA, kf, 0, i);
+      load_v(vf, 0);
+      // ---- half 0 ----
+      softmax_half(sA, pA, m[0], l[0], o0[0], o1[0], 0, valid, with_mfma<1>([&](int i) { qk_step(sB, kf, 1, i); }));
+      load_k(kf, 1);
+      softmax_half(sB, pB, m[1], l[1], o0[1], o1[1], 0, valid, with_mfma<2>([&](int i) {
+        pv_step(0, vf, pA, i);
+        qk_step(sA, kf, 0, i);
+      }));
+      // ---- half 1 ----
+      softmax_half(sA, pA, m[0], l[0], o0[0], o1[0], 32, valid, with_mfma<2>([&](int i) {
+        pv_step(1, vf, pB, i);
+        qk_step(sB, kf, 1, i);
+      }));
+      load_v(vf, 1);
+      softmax_half(sB, pB, m[1], l[1], o0[1], o1[1], 32, valid, with_mfma<1>([&](int i) { pv_step(0, vf, pA, i); }));
 #pragma unroll
-      for (int cb = 0; cb < QB; ++cb) {
-        if (cb >= n_cb) break;
-        if (valid < 32 * half + 32) {  // tokens past the end of the cache / of the frame
+      for (int i = 0; i < 4; ++i) pv_step(1, vf, pB, i);
+    } else {
+      bf16x8 kf[4], vf[2][2];
+      load_k(kf, 0);
 #pragma unroll
-          for (int r = 0; r < 16; ++r)
-            if (32 * half + 16 * (r >> 3) + 8 * hh + (r & 7) >= valid) s[cb][r] = -INFINITY;
-        }
-        // online softmax; the exponent is evaluated in base 2
-        float mx = fmaxf(s[cb][0], s[cb][1]);
+      for (int half = 0; half < 2; ++half) {
+        if (32 * half >= valid) break;
+        f32x16 sv;
 #pragma unroll
-        for (int r = 2; r < 16; r += 2) mx = fmaxf(mx, fmaxf(s[cb][r], s[cb][r + 1]));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        // the reference maximum only moves when some row's maximum grows by more than 2^kLazyLog2;
-        // until then probabilities may exceed 1 (by at most that factor), which fp32 sums and
-        // bf16 products absorb, and the accumulators need no rescaling
-        if (__any((mx - m[cb]) * c2 > kLazyLog2)) {
-          const float m_new = fmaxf(m[cb], mx);
-          const float alpha = __builtin_amdgcn_exp2f((m[cb] - m_new) * c2);
-          l[cb] *= alpha;
-#pragma unroll
-          for (int r = 0; r < 16; ++r) { o0[cb][r] *= alpha; o1[cb][r] *= alpha; }
-          m[cb] = m_new;
-        }
-        const float mc = -m[cb] * c2;
-        float psum = l[cb];
+        for (int i = 0; i < 4; ++i) qk_step(sv, kf, 0, i);
+        load_v(vf, half);
+        if (half == 0 && valid > 32) load_k(kf, 1);
         uint32_t pw[8];
+        softmax_half(sv, pw, m[0], l[0], o0[0], o1[0], 32 * half, valid, with_mfma<0>([](int) {}));
 #pragma unroll
-        for (int r = 0; r < 16; r += 2) {
-          const float p0 = DBG == 1 ? __builtin_fmaf(s[cb][r], c2, mc) : __builtin_amdgcn_exp2f(__builtin_fmaf(s[cb][r], c2, mc));
-          const float p1 = DBG == 1 ? __builtin_fmaf(s[cb][r + 1], c2, mc) : __builtin_amdgcn_exp2f(__builtin_fmaf(s[cb][r + 1], c2, mc));
-          pw[r >> 1] = pack_bf16(p0, p1);
-          // row sum of the ROUNDED probabilities (what the PV product sees): v_dot2c_f32_bf16
-          psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pw[r >> 1]),
-                                                 __builtin_bit_cast(bf16x2, 0x3f803f80u), psum, false);
-        }
-        l[cb] = psum;
-        // O^T += V^T P^T: 2 contraction steps of 16 tokens; P comes straight from the accumulators
-#pragma unroll
-        for (int k2 = 0; k2 < (DBG == 3 ? 1 : 2); ++k2) {
-          const bf16x8 pb = __builtin_bit_cast(bf16x8, make_uint4(pw[4 * k2], pw[4 * k2 + 1], pw[4 * k2 + 2], pw[4 * k2 + 3]));
-          o0[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[k2][0], pb, o0[cb], 0, 0, 0);
-          o1[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[k2][1], pb, o1[cb], 0, 0, 0);
-        }
+        for (int i = 0; i < 4; ++i) pv_step(0, vf, pw, i);
       }
     }
   };
   // Phase 1: this range's tiles of the packed cache; phase 2: its tiles of the frame.  Each phase is
-  // software pipelined on its own: tile t+1 is fetched into registers while tile t is computed,
-  // then converted into the other LDS buffer.
-  int cur = 0;
+  // software pipelined on its own: a tile is fetched into registers while an earlier one is
+  // computed, then converted into a free LDS buffer.
+  int cur = 0;  // two LDS buffers, one barrier per tile
   if (c_begin < c_end) {
     Stage<BITS, G, NH> st;
     fetch_cache_tile<BITS, G, NH>(st, rp, a.pool.Tcap, c_begin, u);
     store_cache_tile<BITS, G, NH>(st, rp.lds + cur * kLdsTile, u);
     for (int t = c_begin; t < c_end; ++t) {
       __syncthreads();  // tile t is in lds[cur]; everybody is done reading lds[cur^1]
-      if (t + 1 < c_end && !dbg_skip_stage) fetch_cache_tile<BITS, G, NH>(st, rp, a.pool.Tcap, t + 1, u);
+      if (t + 1 < c_end) fetch_cache_tile<BITS, G, NH>(st, rp, a.pool.Tcap, t + 1, u);
       compute(cur, min(kTile, Tc - t * kTile));
-      if (t + 1 < c_end && !dbg_skip_stage) store_cache_tile<BITS, G, NH>(st, rp.lds + (cur ^ 1) * kLdsTile, u);
+      if (t + 1 < c_end) store_cache_tile<BITS, G, NH>(st, rp.lds + (cur ^ 1) * kLdsTile, u);
       cur ^= 1;
     }
   }
@@ -416,9 +492,9 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
     store_frame_tile<NH>(st, rp.lds + cur * kLdsTile, is_v, u);  // lds[cur] was last read two barriers ago
     for (int t = f_begin; t < f_end; ++t) {
       __syncthreads();
-      if (t + 1 < f_end && !dbg_skip_stage) fetch_frame_tile<NH>(st, xh, x_st, is_v, t + 1, n, u);
+      if (t + 1 < f_end) fetch_frame_tile<NH>(st, xh, x_st, is_v, t + 1, n, u);
       compute(cur, min(kTile, n - t * kTile));
-      if (t + 1 < f_end && !dbg_skip_stage) store_frame_tile<NH>(st, rp.lds + (cur ^ 1) * kLdsTile, is_v, u);
+      if (t + 1 < f_end) store_frame_tile<NH>(st, rp.lds + (cur ^ 1) * kLdsTile, is_v, u);
       cur ^= 1;
     }
   }
@@ -428,7 +504,7 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
   for (int cb = 0; cb < QB; ++cb) {
     const int q_row = q_row0 + 32 * cb + j;
     const float lsum = l[cb] + __shfl_xor(l[cb], 32);  // the two lane halves saw disjoint tokens
-    if (q_row >= n || (a.variant & 32)) continue;
+    if (q_row >= n) continue;
     if (S == 1) {
       const float inv = 1.0f / lsum;
       uint16_t* op = a.b.out[lb] + ((size_t)h * n + q_row) * kD;
@@ -453,10 +529,6 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
     }
   }
 
-  if (a.dbg) {
-    __syncthreads();
-    if (tid == 0) a.dbg[4 * id + 1] = wall_clock64();
-  }
 }
 
 // Merge of the key-range partials: out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
@@ -493,12 +565,12 @@ __global__ __launch_bounds__(256) void combine_kernel(const AttendArgs a) {
       make_uint2(pack_bf16(acc[0] * inv, acc[1] * inv), pack_bf16(acc[2] * inv, acc[3] * inv));
 }
 
-template <int BITS, int G, int NW, int QB, int DBG = 0>
+template <int BITS, int G, int NW, int QB>
 static hipError_t launch_attend_t(const AttendArgs& a, hipStream_t stream) {
   const int nqb = (a.n + 32 * QB * NW - 1) / (32 * QB * NW);
   const int n_groups = a.b.n_layers * a.pool.H * a.n_splits;
   const int grid = ((n_groups + 7) / 8) * 8 * nqb;
-  hipLaunchKernelGGL((attend_kernel<BITS, G, NW, QB, DBG>), dim3(grid), dim3(NW * 64), 0, stream, a);
+  hipLaunchKernelGGL((attend_kernel<BITS, G, NW, QB>), dim3(grid), dim3(NW * 64), 0, stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (a.n_splits > 1) {
@@ -511,18 +583,17 @@ static hipError_t launch_attend_t(const AttendArgs& a, hipStream_t stream) {
 
 template <int BITS, int G>
 static hipError_t launch_attend_v(const AttendArgs& a, hipStream_t stream) {
-  switch (a.variant & 7) {
+  switch (a.variant) {
     case 1: return launch_attend_t<BITS, G, 4, 1>(a, stream);
-    case 3: return launch_attend_t<BITS, G, 8, 2>(a, stream);
-    case 5: if constexpr (BITS == 4 && G == 64) return launch_attend_t<BITS, G, 4, 2, 1>(a, stream); else return hipErrorInvalidValue;
-    case 6: if constexpr (BITS == 4 && G == 64) return launch_attend_t<BITS, G, 4, 2, 2>(a, stream); else return hipErrorInvalidValue;
-    case 7: if constexpr (BITS == 4 && G == 64) return launch_attend_t<BITS, G, 4, 2, 3>(a, stream); else return hipErrorInvalidValue;
     case 2: return launch_attend_t<BITS, G, 8, 1>(a, stream);
+    case 3: return launch_attend_t<BITS, G, 8, 2>(a, stream);
     default: return launch_attend_t<BITS, G, 4, 2>(a, stream);
   }
 }
 
-int attend_rows_per_workgroup(int variant) { return (variant & 7) == 1 ? 128 : ((variant & 7) == 3 ? 512 : 256); }
+int attend_rows_per_workgroup(int variant) {
+  return variant == 1 ? 128 : (variant == 3 ? 512 : 256);
+}
 
 hipError_t launch_attend(const AttendArgs& a, hipStream_t stream) {
   const int bits = a.pool.bits, G = a.pool.G;

@@ -46,7 +46,6 @@ struct xsv_ctx {
   std::vector<void*> allocs;
   int splits_single = 0, splits_batched = 0;
   int attend_variant = 3;  // 8 waves x 64 query rows per workgroup
-  unsigned long long* dbg = nullptr;
   int max_splits = 1;
   size_t part_rows = 0;  // rows the partial-output workspace holds
   int n_cu = 256;
@@ -128,7 +127,8 @@ int choose_splits(const xsv_ctx* ctx, int n_layers, int Tc, int requested) {
     const int wgs = ((c.tokens_per_frame + rows - 1) / rows) * c.n_heads * n_layers;
     // fill the workgroup slots of the chip (2 per compute unit; 1 for the 8-wave variant) in ONE
     // round, never with ranges shorter than 4 tiles
-    const int slots = ((ctx->attend_variant & 7) >= 2 && (ctx->attend_variant & 7) <= 3 ? 1 : 2) * ctx->n_cu;
+    const int v = ctx->attend_variant;
+    const int slots = (v >= 2 ? 1 : 2) * ctx->n_cu;
     s = std::max(1, slots / wgs);
     s = std::min(s, std::max(1, n_tiles / 4));
   }
@@ -178,7 +178,6 @@ int do_attend(xsv_ctx* ctx, int layer0, int n_layers, const xsv_tensor* q, const
   a.Tc = ctx->layers[layer0].T;
   a.n = ctx->cfg.tokens_per_frame;
   a.variant = ctx->attend_variant;
-  a.dbg = ctx->dbg;
   a.n_splits = choose_splits(ctx, n_layers, a.Tc, splits_req);
   a.qscale = ctx->cfg.softmax_scale * 1.4426950408889634f;
   if (launch_attend(a, ctx->stream) != hipSuccess) return hip_fail(ctx);
@@ -398,20 +397,8 @@ int xsv_set_attend_splits(xsv_ctx* ctx, int per_layer_calls, int batched_calls) 
   return XSV_OK;
 }
 
-// debugging aid: per-workgroup timestamps of the last attention launch (host buffer of 4*max_wgs u64)
-int xsv_debug_times(xsv_ctx* ctx, unsigned long long* host, int max_wgs) {
-  if (!ctx) return XSV_ERR_ARG;
-  if (!ctx->dbg) {
-    if (dev_alloc(ctx, &ctx->dbg, (size_t)4 * 16384, true) != XSV_OK) return XSV_ERR_OOM;
-    return XSV_OK;
-  }
-  if (hipStreamSynchronize(ctx->stream) != hipSuccess) return XSV_ERR_HIP;
-  if (host && hipMemcpy(host, ctx->dbg, (size_t)4 * std::min(max_wgs, 16384) * 8, hipMemcpyDeviceToHost) != hipSuccess) return XSV_ERR_HIP;
-  return XSV_OK;
-}
-
 int xsv_set_attend_variant(xsv_ctx* ctx, int variant) {
-  if (!ctx || variant < 0 || variant > 63) return XSV_ERR_ARG;
+  if (!ctx || variant < 0 || variant > 3) return XSV_ERR_ARG;
   ctx->attend_variant = variant;
   return XSV_OK;
 }

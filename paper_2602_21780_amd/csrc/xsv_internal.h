@@ -101,7 +101,6 @@ struct AttendArgs {
   int Tc, n, n_splits;
   int variant;   // 0: 4 waves x 64 queries, 1: 4 waves x 32 queries, 2: 8 waves x 32 queries per workgroup
   float qscale;  // softmax scale * log2(e)
-  unsigned long long* dbg;  // optional [workgroup][4]: start, end, hw id, xcc id
 };
 hipError_t launch_attend(const AttendArgs& a, hipStream_t stream);
 int attend_rows_per_workgroup(int variant);
