@@ -47,6 +47,7 @@ def main():
     ap.add_argument("--splits", type=int, default=0, help="key ranges per attention launch (0 = auto)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-overlap", action="store_true", help="run the prune chain after attention on one stream")
+    ap.add_argument("--side-cus", type=int, default=-1, help="compute units left to the overlapped prune chain (-1 = library default)")
     ap.add_argument("--stage-frames", type=int, default=6, help="frames of the per-stage event-timed pass")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -75,6 +76,8 @@ def main():
     ctx.set_attend_splits(args.splits, args.splits)
     if args.no_overlap:
         ctx.set_overlap(False)
+    if args.side_cus >= 0:
+        ctx.set_side_cus(args.side_cus)
     packed = [ctx.pack_layers(q, k, v, out) for (q, k, v) in frames]
     torch.cuda.synchronize()
 

@@ -102,8 +102,9 @@ int xsv_quantize(xsv_ctx* ctx, int layer, xsv_tensor k_new, xsv_tensor v_new);
 
 /* The three calls above for one layer.  Attention runs on the context's stream while score, select
  * and re-quantization run concurrently on a stream owned by the context (they read the same inputs
- * and write the layer's other cache buffer); when the call returns, the context's stream is ordered
- * after both, so the usual "valid until the stream has passed the call" rule holds. */
+ * and write the layer's other cache buffer).  In the default overlap mode (1) the context's stream is
+ * ordered after both when the call returns, so the usual "valid until the stream has passed the
+ * call" rule holds; see xsv_set_overlap for the mode that defers this join. */
 int xsv_step(xsv_ctx* ctx, int layer, xsv_tensor q, xsv_tensor k_new, xsv_tensor v_new, void* out);
 
 /* One frame through ALL layers with layer-batched launches (arrays of n_layers entries; every
@@ -113,12 +114,29 @@ int xsv_step(xsv_ctx* ctx, int layer, xsv_tensor q, xsv_tensor k_new, xsv_tensor
 int xsv_step_all_layers(xsv_ctx* ctx, const xsv_tensor* q, const xsv_tensor* k_new, const xsv_tensor* v_new,
                         void* const* out);
 
-/* Tuning: number of key ranges one (head, query block) is split into by xsv_dequant_attend
- * (partial results are merged by a second kernel).  0 = choose from the launch size.  1..16. */
+/* Tuning: number of equal key ranges every (head, block of query rows) is cut into by the attention
+ * kernel (partial results are merged by a second kernel), 1..16.  0 (default) = one workgroup per
+ * slot of the chip, the key tiles of all (head, query block) pairs dealt out evenly among them. */
 int xsv_set_attend_splits(xsv_ctx* ctx, int per_layer_calls, int batched_calls);
-/* Tuning: 0 = xsv_step / xsv_step_all_layers run everything on the context's stream, in order;
- * 1 (default) = the score/select/re-quantize chain overlaps the attention kernel. */
-int xsv_set_overlap(xsv_ctx* ctx, int enabled);
+/* How xsv_step / xsv_step_all_layers order the score/select/re-quantize chain:
+ *   0  everything on the context's stream, in order;
+ *   1  (default) the chain overlaps the attention kernel on the context's side stream and the
+ *      context's stream waits for it before the call returns;
+ *   2  as 1, but the wait is deferred: the context's stream waits for the chain of a layer only
+ *      before the next call that touches that layer, or in xsv_join.  A cross-stream wait costs
+ *      more than most of these kernels run, and the next LAYER's attention does not depend on this
+ *      layer's chain — only this layer's next FRAME does.  In this mode q, k_new and v_new of a step
+ *      must stay valid and unchanged until the context's stream has passed the next call for that
+ *      layer or an xsv_join; `out` follows the usual rule.
+ * Switching the mode joins first. */
+int xsv_set_overlap(xsv_ctx* ctx, int mode);
+/* Orders the context's stream after all side-stream work enqueued so far (no host wait).  A no-op
+ * unless overlap mode 2 has steps outstanding. */
+int xsv_join(xsv_ctx* ctx);
+/* Tuning: compute units the attention launch of xsv_step / xsv_step_all_layers leaves free for the
+ * overlapped score/select/re-quantize chain (default 64; 0 .. half the chip).  Without spare units
+ * the chain only starts when attention drains.  Ignored when overlap is off or splits are fixed. */
+int xsv_set_side_cus(xsv_ctx* ctx, int compute_units);
 /* Tuning: workgroup shape of the attention kernel (waves x query rows per wave).  3 (default) = 8 x 64,
  * 0 = 4 x 64, 1 = 4 x 32, 2 = 8 x 32.  Other values: XSV_ERR_ARG.  Results agree to rounding. */
 int xsv_set_attend_variant(xsv_ctx* ctx, int variant);

@@ -16,9 +16,13 @@
 //   cost is shared by NW*QB*32 queries (half of the threads stage K, the other half V, with the
 //   same code on mirrored layouts).  LDS is double buffered; the next tile's packed codes and
 //   group parameters are fetched into registers before the current tile's MFMAs are issued.
-//   blockIdx is remapped so that all query blocks of one (layer, head, key range) land on the same
-//   XCD and share its L2.  With n_splits > 1 each key range writes unnormalized partials that
-//   combine_kernel merges.
+//   Partition.  A unit is one (layer, head, block of NW*QB*32 query rows); its work is its key tiles.
+//   All units' tiles form one line of n_units * n_tiles items, cut into gridDim.x equal pieces, one
+//   per workgroup — so any number of workgroups (a full chip, or a chip minus the compute units
+//   left to the kernels that run beside this one) gets the same amount of work.  A workgroup's
+//   piece may end one unit and begin the next; it handles them one after the other.  A unit
+//   covered by one piece is normalized and written directly; otherwise each piece writes
+//   unnormalized partials that combine_kernel merges.
 #include <type_traits>
 
 #include "xsv_internal.h"
@@ -35,6 +39,7 @@ constexpr float kNegBig = -1.0e30f;
 constexpr float kLazyLog2 = 8.0f;  // headroom of the lazily updated softmax reference, in powers of two
 
 typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   const f32x2 v = {a, b};  // one v_cvt_pk_bf16_f32: round to nearest even, a in the low half
@@ -250,6 +255,17 @@ struct MfmaHook {
 template <int N, typename F>
 __device__ __forceinline__ MfmaHook<N, F> with_mfma(F f) { return MfmaHook<N, F>{f}; }
 
+// ---- partition of the (unit, tile) line over the workgroups -----------------------------------------
+struct Partition {
+  long long total;  // n_units * n_tiles
+  int n_tiles, n_wgs;
+  __host__ __device__ long long begin(int w) const { return total * w / n_wgs; }
+  // workgroup whose piece holds item x
+  __host__ __device__ int owner(long long x) const { return (int)(((x + 1) * n_wgs + total - 1) / total) - 1; }
+  __host__ __device__ int first_wg(int unit) const { return owner((long long)unit * n_tiles); }
+  __host__ __device__ int last_wg(int unit) const { return owner((long long)(unit + 1) * n_tiles - 1); }
+};
+
 // ---- the kernel ----------------------------------------------------------------------------------
 template <int BITS, int G, int NW, int QB>
 __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
@@ -258,28 +274,33 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
   __shared__ __attribute__((aligned(16))) uint16_t lds_k[2][kLdsTile];
   __shared__ __attribute__((aligned(16))) uint16_t lds_v[2][kLdsTile];
 
-  const int H = a.pool.H, n = a.n, Tc = a.Tc, S = a.n_splits;
+  const int H = a.pool.H, n = a.n, Tc = a.Tc;
   const int nqb = (n + kRowsWG - 1) / kRowsWG;
-  const int n_groups = a.b.n_layers * H * S;
-  // XCD-aware decode: ids with equal (id % 8) run on the same XCD; give them the same keys.
-  const int id = blockIdx.x;
-  const int chunk = id / (8 * nqb), within = id % (8 * nqb);
-  const int grp = chunk * 8 + (within & 7);
-  const int qb = within >> 3;
-  if (grp >= n_groups) return;
-  const int split = grp % S;
-  const int h = (grp / S) % H;
-  const int lb = grp / (S * H);
-
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int j = lane & 31, hh = lane >> 5;
-
-  const LayerCache lc = layer_cache(a.pool, a.b.src_buf(lb), a.b.layer0 + lb);
-  const uint16_t* qh = a.b.q[lb] + (size_t)h * a.b.q_sh;
-
+  const int krow = tau(j);
+  const float c2 = a.qscale;  // softmax scale * log2(e): p = 2^(c2 * (logit - max))
   // staging role of this thread: first half of the workgroup K, second half V
   const bool is_v = tid >= NH;
   const int u = is_v ? tid - NH : tid;
+
+  // tiles of a unit: cache blocks, then the frame's own tokens (each range padded to 64 on its own)
+  const int n_ct = (Tc + kTile - 1) / kTile, n_ft = (n + kTile - 1) / kTile;
+  const Partition part{(long long)a.b.n_layers * H * nqb * (n_ct + n_ft), n_ct + n_ft, (int)gridDim.x};
+  const long long piece_end = part.begin(blockIdx.x + 1);
+
+  for (long long pos = part.begin(blockIdx.x); pos < piece_end;) {
+  const int unit = (int)(pos / part.n_tiles);
+  const int t_begin = (int)(pos - (long long)unit * part.n_tiles);
+  const int t_end = (int)min((long long)part.n_tiles, t_begin + (piece_end - pos));
+  pos += t_end - t_begin;
+  const int qb = unit % nqb, h = (unit / nqb) % H, lb = unit / (nqb * H);
+  const bool whole = t_begin == 0 && t_end == part.n_tiles;
+  const int c_begin = min(t_begin, n_ct), c_end = min(t_end, n_ct);
+  const int f_begin = max(t_begin, n_ct) - n_ct, f_end = max(t_end, n_ct) - n_ct;
+
+  const LayerCache lc = layer_cache(a.pool, a.b.src_buf(lb), a.b.layer0 + lb);
+  const uint16_t* qh = a.b.q[lb] + (size_t)h * a.b.q_sh;
   RolePtrs rp;
   {
     const size_t head_rows = (size_t)h * a.pool.Tcap;
@@ -291,12 +312,6 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
   }
   const uint16_t* xh = is_v ? a.b.v[lb] + (size_t)h * a.b.v_sh : a.b.k[lb] + (size_t)h * a.b.k_sh;
   const int64_t x_st = is_v ? a.b.v_st : a.b.k_st;
-
-  // tiles: cache blocks, then the frame's own tokens (each range padded to 64 on its own).  A key
-  // range takes an equal share of BOTH kinds, so that every range costs the same.
-  const int n_ct = (Tc + kTile - 1) / kTile, n_ft = (n + kTile - 1) / kTile;
-  const int c_begin = (int)((long long)n_ct * split / S), c_end = (int)((long long)n_ct * (split + 1) / S);
-  const int f_begin = (int)((long long)n_ft * split / S), f_end = (int)((long long)n_ft * (split + 1) / S);
 
   // query fragments (B operand): lane holds channels 16*ks + 8*hh .. +8 of its query row, as given
   // (the softmax scale is applied to the fp32 logits, so no extra bf16 rounding enters)
@@ -312,7 +327,6 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
   }
   // query blocks of this wave that hold at least one real row (wave-uniform)
   const int n_cb = q_row0 >= n ? 0 : min(QB, (n - q_row0 + 31) / 32);
-  const float c2 = a.qscale;  // softmax scale * log2(e): p = 2^(c2 * (logit - max))
 
   f32x16 o0[QB], o1[QB];
   float m[QB], l[QB];  // running max of the raw logits, this lane's share of the row sum
@@ -323,23 +337,26 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
     m[cb] = kNegBig;
     l[cb] = 0.f;
   }
-  const int krow = tau(j);
-
   // softmax of one query block over the 32 tokens of a half-step: masks tokens >= valid, moves the
   // (lazy) reference maximum, exponentiates into packed bf16 and adds the row sums.  `hook(i)`,
   // i = 0..3, is called before each quarter of the exponentials: the caller issues MFMAs there, so
   // that the matrix pipe works underneath this arithmetic.
-  auto softmax_half = [&](f32x16& sv, uint32_t (&pw)[8], float& mref, float& lsum, f32x16& oa, f32x16& ob, int tok0,
+  auto softmax_half = [&](f32x16& sv, u32x4 (&pb)[2], float& mref, float& lsum, f32x16& oa, f32x16& ob, int tok0,
                           int valid, auto&& hook) {
     if (valid < tok0 + 32) {  // tokens past the end of the cache / of the frame
+      // (the limit passes through an opaque move so that the 16 compares stay inside this rarely
+      // taken branch instead of being hoisted into every tile)
+      int lim = valid - tok0;
+      asm volatile("" : "+s"(lim));
+      lim -= 8 * hh;
 #pragma unroll
       for (int r = 0; r < 16; ++r)
-        if (tok0 + 16 * (r >> 3) + 8 * hh + (r & 7) >= valid) sv[r] = -INFINITY;
+        if (16 * (r >> 3) + (r & 7) >= lim) sv[r] = -INFINITY;
     }
-    float mx = fmaxf(sv[0], sv[1]);
+    float mx = fmaxf(fmaxf(sv[0], sv[1]), sv[2]);  // v_max3 chain
 #pragma unroll
-    for (int r = 2; r < 16; r += 2) mx = fmaxf(mx, fmaxf(sv[r], sv[r + 1]));
-    mx = xhalf_max(mx);
+    for (int r = 3; r < 15; r += 2) mx = fmaxf(fmaxf(mx, sv[r]), sv[r + 1]);
+    mx = xhalf_max(fmaxf(mx, sv[15]));
     // the reference maximum only moves when some row's maximum grows by more than 2^kLazyLog2;
     // until then probabilities may exceed 1 (by at most that factor), which fp32 sums and
     // bf16 products absorb, and the accumulators need no rescaling
@@ -360,16 +377,16 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
       for (int r = 4 * q4; r < 4 * q4 + 4; r += 2) {
         const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r], c2, mc));
         const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r + 1], c2, mc));
-        pw[r >> 1] = pack_bf16(p0, p1);
+        const uint32_t w = pack_bf16(p0, p1);
+        pb[r >> 3][(r >> 1) & 3] = w;  // registers r = 8*k2 .. 8*k2+7 are the B operand of token step k2
         // row sum of the ROUNDED probabilities (what the PV product sees): v_dot2c_f32_bf16
-        psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pw[r >> 1]),
-                                               __builtin_bit_cast(bf16x2, 0x3f803f80u), psum, false);
+        psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), __builtin_bit_cast(bf16x2, 0x3f803f80u),
+                                               psum, false);
       }
     }
     // keep this block's probabilities in this block (the compiler would otherwise sink the
     // exponentials down to their consumer, next to the MFMAs they are meant to overlap with)
-#pragma unroll
-    for (int i = 0; i < 8; ++i) asm volatile("" : "+v"(pw[i]));
+    asm volatile("" : "+v"(pb[0]), "+v"(pb[1]));
     // prescribed issue order of this block, per quarter: its MFMAs spread between its 12 vector
     // instructions (4 fma, 4 exp, 2 convert, 2 dot) — the MFMAs execute while the VALU works
     constexpr int kMfmaPerQuarter = std::remove_reference_t<decltype(hook)>::kMfma;
@@ -417,11 +434,11 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
       sv = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i], qf[cb][i], i == 0 ? zero : sv, 0, 0, 0);
     };
     // step i (0..3) of O^T += V^T P^T for one query block: token step i/2, channel half i%2
-    auto pv_step = [&](int cb, const bf16x8 (&vf)[2][2], const uint32_t (&pw)[8], int i) {
+    auto pv_step = [&](int cb, const bf16x8 (&vf)[2][2], const u32x4 (&pb)[2], int i) {
       const int k2 = i >> 1;
-      const bf16x8 pb = __builtin_bit_cast(bf16x8, make_uint4(pw[4 * k2], pw[4 * k2 + 1], pw[4 * k2 + 2], pw[4 * k2 + 3]));
-      if (i & 1) o1[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[k2][1], pb, o1[cb], 0, 0, 0);
-      else o0[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[k2][0], pb, o0[cb], 0, 0, 0);
+      const bf16x8 p = __builtin_bit_cast(bf16x8, pb[k2]);
+      if (i & 1) o1[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[k2][1], p, o1[cb], 0, 0, 0);
+      else o0[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[k2][0], p, o0[cb], 0, 0, 0);
     };
 
     if constexpr (QB == 2) {
@@ -431,7 +448,7 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
       // Blocks past the end of the frame are computed on clamped rows and never stored.
       bf16x8 kf[4], vf[2][2];
       f32x16 sA, sB;
-      uint32_t pA[8], pB[8];
+      u32x4 pA[2], pB[2];
       load_k(kf, 0);
 #pragma unroll
       for (int i = 0; i < 4; ++i) qk_step(sA, kf, 0, i);
@@ -463,7 +480,7 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
         for (int i = 0; i < 4; ++i) qk_step(sv, kf, 0, i);
         load_v(vf, half);
         if (half == 0 && valid > 32) load_k(kf, 1);
-        uint32_t pw[8];
+        u32x4 pw[2];
         softmax_half(sv, pw, m[0], l[0], o0[0], o1[0], 32 * half, valid, with_mfma<0>([](int) {}));
 #pragma unroll
         for (int i = 0; i < 4; ++i) pv_step(0, vf, pw, i);
@@ -473,7 +490,8 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
   // Phase 1: this range's tiles of the packed cache; phase 2: its tiles of the frame.  Each phase is
   // software pipelined on its own: a tile is fetched into registers while an earlier one is
   // computed, then converted into a free LDS buffer.
-  int cur = 0;  // two LDS buffers, one barrier per tile
+  __syncthreads();  // the previous unit's last tile has been read by everybody
+  int cur = 0;      // two LDS buffers, one barrier per tile
   if (c_begin < c_end) {
     Stage<BITS, G, NH> st;
     fetch_cache_tile<BITS, G, NH>(st, rp, a.pool.Tcap, c_begin, u);
@@ -505,7 +523,7 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
     const int q_row = q_row0 + 32 * cb + j;
     const float lsum = l[cb] + __shfl_xor(l[cb], 32);  // the two lane halves saw disjoint tokens
     if (q_row >= n) continue;
-    if (S == 1) {
+    if (whole) {
       const float inv = 1.0f / lsum;
       uint16_t* op = a.b.out[lb] + ((size_t)h * n + q_row) * kD;
 #pragma unroll
@@ -517,7 +535,8 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
                                                             pack_bf16(o1[cb][4 * q4 + 2] * inv, o1[cb][4 * q4 + 3] * inv));
       }
     } else {
-      const size_t row = (((size_t)split * a.b.n_layers + lb) * H + h) * n + q_row;
+      const int piece = (int)blockIdx.x - part.first_wg(unit);
+      const size_t row = (((size_t)piece * a.b.n_layers + lb) * H + h) * n + q_row;
       float* op = a.ws.attn_o + row * kD;
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
@@ -528,20 +547,30 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
       if (hh == 0) *reinterpret_cast<float2*>(a.ws.attn_ml + row * 2) = make_float2(m[cb] * c2, lsum);
     }
   }
+  }  // units of this workgroup's piece
 
 }
 
-// Merge of the key-range partials: out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
+// Merge of the pieces of every unit that was cut:  out = sum_p 2^(m_p - M) O_p / sum_p 2^(m_p - M) l_p.
 // (A separate launch on purpose: a device-wide release/acquire inside the attention kernel costs an
 // L2 write-back per workgroup on this multi-die part, far more than a second small kernel.)
 __global__ __launch_bounds__(256) void combine_kernel(const AttendArgs a) {
-  const int H = a.pool.H, n = a.n, S = a.n_splits;
+  const int H = a.pool.H, n = a.n;
   const size_t rows = (size_t)a.b.n_layers * H * n;
   const size_t gid = (size_t)blockIdx.x * 256 + threadIdx.x;
   const size_t row = gid >> 4;
   const int c = (int)(gid & 15) * 4;
   if (row >= rows) return;
-  float ms[16], ls[16];
+  const int lb = (int)(row / ((size_t)H * n));
+  const size_t in_layer = row - (size_t)lb * H * n;
+  const int h = (int)(in_layer / n), q_row = (int)(in_layer - (size_t)h * n);
+  const int nqb = (n + a.rows_wg - 1) / a.rows_wg;
+  const int n_tiles = (a.Tc + kTile - 1) / kTile + (n + kTile - 1) / kTile;
+  const Partition part{(long long)a.b.n_layers * H * nqb * n_tiles, n_tiles, a.n_wgs};
+  const int unit = (lb * H + h) * nqb + q_row / a.rows_wg;
+  const int S = part.last_wg(unit) - part.first_wg(unit) + 1;
+  if (S == 1) return;  // written by the attention kernel itself
+  float ms[kMaxPieces], ls[kMaxPieces];
   float M = kNegBig;
 #pragma unroll 4
   for (int s = 0; s < S; ++s) {
@@ -559,21 +588,16 @@ __global__ __launch_bounds__(256) void combine_kernel(const AttendArgs a) {
     acc[0] += w * o.x; acc[1] += w * o.y; acc[2] += w * o.z; acc[3] += w * o.w;
   }
   const float inv = 1.0f / L;
-  const int lb = (int)(row / ((size_t)H * n));
-  const size_t in_layer = row - (size_t)lb * H * n;
   *reinterpret_cast<uint2*>(a.b.out[lb] + in_layer * kD + c) =
       make_uint2(pack_bf16(acc[0] * inv, acc[1] * inv), pack_bf16(acc[2] * inv, acc[3] * inv));
 }
 
 template <int BITS, int G, int NW, int QB>
 static hipError_t launch_attend_t(const AttendArgs& a, hipStream_t stream) {
-  const int nqb = (a.n + 32 * QB * NW - 1) / (32 * QB * NW);
-  const int n_groups = a.b.n_layers * a.pool.H * a.n_splits;
-  const int grid = ((n_groups + 7) / 8) * 8 * nqb;
-  hipLaunchKernelGGL((attend_kernel<BITS, G, NW, QB>), dim3(grid), dim3(NW * 64), 0, stream, a);
+  hipLaunchKernelGGL((attend_kernel<BITS, G, NW, QB>), dim3(a.n_wgs), dim3(NW * 64), 0, stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  if (a.n_splits > 1) {
+  if (a.cut) {
     const size_t threads = (size_t)a.b.n_layers * a.pool.H * a.n * 16;
     hipLaunchKernelGGL(combine_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream, a);
     e = hipGetLastError();
@@ -593,6 +617,31 @@ static hipError_t launch_attend_v(const AttendArgs& a, hipStream_t stream) {
 
 int attend_rows_per_workgroup(int variant) {
   return variant == 1 ? 128 : (variant == 3 ? 512 : 256);
+}
+
+AttendPlan plan_attend(int variant, int n_layers, int H, int n, int Tc, int want_wgs, size_t part_rows) {
+  const int rows_wg = attend_rows_per_workgroup(variant);
+  const int nqb = (n + rows_wg - 1) / rows_wg;
+  const int n_units = n_layers * H * nqb;
+  const int n_tiles = (Tc + kTile - 1) / kTile + (n + kTile - 1) / kTile;
+  const long long total = (long long)n_units * n_tiles;
+  // a piece never shorter than 4 tiles (unless a whole unit is), never more workgroups than items
+  long long w = std::max<long long>(1, std::min<long long>(want_wgs, std::max<long long>(n_units, total / 4)));
+  // the partial workspace holds `fit` pieces of every row, the merge at most kMaxPieces
+  const int fit = (int)std::min<size_t>(kMaxPieces, part_rows / ((size_t)n_layers * H * n));
+  AttendPlan p{};
+  for (;; --w) {
+    const Partition part{total, n_tiles, (int)w};
+    int worst = 1;
+    for (int unit = 0; unit < n_units; ++unit) worst = std::max(worst, part.last_wg(unit) - part.first_wg(unit) + 1);
+    if (worst <= fit || w == 1) {
+      p.n_wgs = (int)w;
+      p.rows_wg = rows_wg;
+      p.max_pieces = worst;
+      return p;
+    }
+    if (w > n_units) w = std::max<long long>(n_units + 1, w - w / 8);  // then --w
+  }
 }
 
 hipError_t launch_attend(const AttendArgs& a, hipStream_t stream) {

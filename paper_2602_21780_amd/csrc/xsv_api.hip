@@ -39,14 +39,18 @@ struct xsv_ctx {
   hipStream_t side = nullptr;
   hipEvent_t ev_fork = nullptr, ev_join = nullptr;
   hipStream_t work = nullptr;  // stream the score/quantize launchers currently enqueue on
-  bool overlap = true;
+  int overlap = 1;             // 0: one stream; 1: side stream, joined before the call returns; 2: joined lazily
+  // overlap == 2: ev_chain[l] is recorded on `side` behind the chain of a step that began at layer l;
+  // pending[l] >= 0 names the event `stream` still has to wait for before it may touch layer l
+  std::vector<hipEvent_t> ev_chain;
+  std::vector<int> pending;
   CachePool pool;
   Workspace ws;
   std::vector<LayerState> layers;
   std::vector<void*> allocs;
   int splits_single = 0, splits_batched = 0;
   int attend_variant = 3;  // 8 waves x 64 query rows per workgroup
-  int max_splits = 1;
+  int side_cus = 64;  // compute units xsv_step leaves to the prune chain while attention runs
   size_t part_rows = 0;  // rows the partial-output workspace holds
   int n_cu = 256;
   bool broken = false;
@@ -86,8 +90,23 @@ void free_all(xsv_ctx* ctx) {
   if (ctx->side) (void)hipStreamDestroy(ctx->side);
   if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
   if (ctx->ev_join) (void)hipEventDestroy(ctx->ev_join);
+  for (hipEvent_t e : ctx->ev_chain) (void)hipEventDestroy(e);
+  ctx->ev_chain.clear();
   ctx->side = nullptr;
   ctx->ev_fork = ctx->ev_join = nullptr;
+}
+
+// Orders the context's stream after the side-stream work still outstanding for layers [l0, l0 + n).
+int join_layers(xsv_ctx* ctx, int l0, int n) {
+  int last = -1;
+  for (int l = l0; l < l0 + n; ++l) {
+    const int e = ctx->pending[l];
+    if (e < 0) continue;
+    if (e != last && hipStreamWaitEvent(ctx->stream, ctx->ev_chain[e], 0) != hipSuccess) return hip_fail(ctx);
+    last = e;
+    ctx->pending[l] = -1;
+  }
+  return XSV_OK;
 }
 
 // What a step does to the cache length (paper Sec. 3.2: prune once T exceeds the budget; first and
@@ -118,23 +137,16 @@ PrunePlan plan_for(const xsv_config& c, const LayerState& L) {
   return p;
 }
 
-int choose_splits(const xsv_ctx* ctx, int n_layers, int Tc, int requested) {
+// Workgroups of one attention launch.  requested > 0: every unit is cut into that many equal key
+// ranges.  Otherwise one workgroup per slot of the chip (2 per compute unit for the 4-wave shapes, 1
+// for the 8-wave ones), minus the compute units left to kernels running beside it.
+AttendPlan choose_grid(const xsv_ctx* ctx, int n_layers, int Tc, int requested, int spare_cus) {
   const xsv_config& c = ctx->cfg;
-  const int n_tiles = (Tc + kTile - 1) / kTile + (c.tokens_per_frame + kTile - 1) / kTile;
-  int s = requested;
-  if (s <= 0) {
-    const int rows = attend_rows_per_workgroup(ctx->attend_variant);
-    const int wgs = ((c.tokens_per_frame + rows - 1) / rows) * c.n_heads * n_layers;
-    // fill the workgroup slots of the chip (2 per compute unit; 1 for the 8-wave variant) in ONE
-    // round, never with ranges shorter than 4 tiles
-    const int v = ctx->attend_variant;
-    const int slots = (v >= 2 ? 1 : 2) * ctx->n_cu;
-    s = std::max(1, slots / wgs);
-    s = std::min(s, std::max(1, n_tiles / 4));
-  }
-  const size_t rows_per_split = (size_t)n_layers * c.n_heads * c.tokens_per_frame;
-  s = std::max(1, std::min({s, ctx->max_splits, n_tiles, (int)(ctx->part_rows / rows_per_split)}));
-  return s;
+  const int rows = attend_rows_per_workgroup(ctx->attend_variant);
+  const int n_units = ((c.tokens_per_frame + rows - 1) / rows) * c.n_heads * n_layers;
+  const int per_cu = ctx->attend_variant >= 2 ? 1 : 2;
+  const int want = requested > 0 ? n_units * requested : per_cu * std::max(ctx->n_cu / 2, ctx->n_cu - spare_cus);
+  return plan_attend(ctx->attend_variant, n_layers, c.n_heads, c.tokens_per_frame, Tc, want, ctx->part_rows);
 }
 
 int fill_batch(xsv_ctx* ctx, Batch& b, int layer0, int n_layers, const xsv_tensor* q, const xsv_tensor* k,
@@ -169,7 +181,7 @@ int fill_batch(xsv_ctx* ctx, Batch& b, int layer0, int n_layers, const xsv_tenso
 
 // The three stages for layers [layer0, layer0 + n_layers), which must be in step with each other.
 int do_attend(xsv_ctx* ctx, int layer0, int n_layers, const xsv_tensor* q, const xsv_tensor* k, const xsv_tensor* v,
-              void* const* out, int splits_req) {
+              void* const* out, int splits_req, int spare_cus) {
   AttendArgs a{};
   int rc = fill_batch(ctx, a.b, layer0, n_layers, q, k, v, out);
   if (rc != XSV_OK) return rc;
@@ -178,7 +190,10 @@ int do_attend(xsv_ctx* ctx, int layer0, int n_layers, const xsv_tensor* q, const
   a.Tc = ctx->layers[layer0].T;
   a.n = ctx->cfg.tokens_per_frame;
   a.variant = ctx->attend_variant;
-  a.n_splits = choose_splits(ctx, n_layers, a.Tc, splits_req);
+  const AttendPlan plan = choose_grid(ctx, n_layers, a.Tc, splits_req, spare_cus);
+  a.n_wgs = plan.n_wgs;
+  a.rows_wg = plan.rows_wg;
+  a.cut = plan.max_pieces > 1;
   a.qscale = ctx->cfg.softmax_scale * 1.4426950408889634f;
   if (launch_attend(a, ctx->stream) != hipSuccess) return hip_fail(ctx);
   for (int i = 0; i < n_layers; ++i) ctx->layers[layer0 + i].phase = kAttended;
@@ -324,6 +339,16 @@ int xsv_create(const xsv_config* cfg, void* hip_stream, xsv_ctx** out) {
     delete ctx;
     return XSV_ERR_HIP;
   }
+  ctx->pending.assign(c.n_layers, -1);
+  for (int l = 0; l < c.n_layers; ++l) {
+    hipEvent_t e = nullptr;
+    if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) {
+      free_all(ctx);
+      delete ctx;
+      return XSV_ERR_HIP;
+    }
+    ctx->ev_chain.push_back(e);
+  }
   int dev = 0;
   hipDeviceProp_t prop;
   if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) {
@@ -359,7 +384,6 @@ int xsv_create(const xsv_config* cfg, void* hip_stream, xsv_ctx** out) {
   A(&w.keep, (size_t)c.n_layers * w.scores_stride, true);
   A(&w.qpart, (size_t)c.n_layers * w.qpart_rows * kD, true);
   // partial attention outputs: up to 16 key ranges for one layer, or 2 per layer when batched
-  ctx->max_splits = 16;
   const size_t part_rows = (size_t)std::max(16, 2 * std::min(c.n_layers, kMaxBatch)) * c.n_heads * n;
   ctx->part_rows = part_rows;
   A(&w.attn_o, part_rows * kD, false);
@@ -386,14 +410,28 @@ int xsv_destroy(xsv_ctx* ctx) {
 int xsv_reset(xsv_ctx* ctx) {
   if (!ctx) return XSV_ERR_ARG;
   if (ctx->broken) return XSV_ERR_HIP;
+  const int rc = join_layers(ctx, 0, ctx->cfg.n_layers);
+  if (rc != XSV_OK) return rc;
   for (LayerState& L : ctx->layers) L = LayerState();
   return XSV_OK;
+}
+
+int xsv_join(xsv_ctx* ctx) {
+  if (!ctx) return XSV_ERR_ARG;
+  if (ctx->broken) return XSV_ERR_HIP;
+  return join_layers(ctx, 0, ctx->cfg.n_layers);
 }
 
 int xsv_set_attend_splits(xsv_ctx* ctx, int per_layer_calls, int batched_calls) {
   if (!ctx || per_layer_calls < 0 || per_layer_calls > 16 || batched_calls < 0 || batched_calls > 16) return XSV_ERR_ARG;
   ctx->splits_single = per_layer_calls;
   ctx->splits_batched = batched_calls;
+  return XSV_OK;
+}
+
+int xsv_set_side_cus(xsv_ctx* ctx, int compute_units) {
+  if (!ctx || compute_units < 0 || compute_units > ctx->n_cu / 2) return XSV_ERR_ARG;
+  ctx->side_cus = compute_units;
   return XSV_OK;
 }
 
@@ -408,8 +446,9 @@ int xsv_dequant_attend(xsv_ctx* ctx, int layer, xsv_tensor q, xsv_tensor k_new, 
   if (rc != XSV_OK) return rc;
   if (ctx->layers[layer].phase != kIdle) return XSV_ERR_STATE;
   if ((rc = check_capacity(ctx, layer)) != XSV_OK) return rc;
+  if ((rc = join_layers(ctx, layer, 1)) != XSV_OK) return rc;
   void* outs[1] = {out};
-  return do_attend(ctx, layer, 1, &q, &k_new, &v_new, outs, ctx->splits_single);
+  return do_attend(ctx, layer, 1, &q, &k_new, &v_new, outs, ctx->splits_single, 0);
 }
 
 int xsv_score_prune(xsv_ctx* ctx, int layer, xsv_tensor q) {
@@ -427,23 +466,29 @@ int xsv_quantize(xsv_ctx* ctx, int layer, xsv_tensor k_new, xsv_tensor v_new) {
   return do_quantize(ctx, layer, 1, &k_new, &v_new);
 }
 
-// attention on the context's stream, score → select → re-quantize concurrently on the side stream;
-// on return the context's stream is ordered after both
+// attention on the context's stream, score → select → re-quantize concurrently on the side stream.
+// overlap 1: on return the context's stream is ordered after both.  overlap 2: the context's stream
+// only waits for a layer's chain when it next needs that layer (or in xsv_join).
 static int step_layers(xsv_ctx* ctx, int layer0, int n_layers, const xsv_tensor* q, const xsv_tensor* k,
                        const xsv_tensor* v, void* const* out, int splits) {
-  const bool fork = ctx->overlap;
+  const bool fork = ctx->overlap != 0;
+  int rc = join_layers(ctx, layer0, n_layers);  // the previous frame's chain wrote the cache read now
+  if (rc != XSV_OK) return rc;
   if (fork) {
     if (hipEventRecord(ctx->ev_fork, ctx->stream) != hipSuccess || hipStreamWaitEvent(ctx->side, ctx->ev_fork, 0) != hipSuccess)
       return hip_fail(ctx);
   }
-  int rc = do_attend(ctx, layer0, n_layers, q, k, v, out, splits);
+  rc = do_attend(ctx, layer0, n_layers, q, k, v, out, splits, fork ? ctx->side_cus : 0);
   if (rc == XSV_OK) {
     ctx->work = fork ? ctx->side : ctx->stream;
     rc = do_score_prune(ctx, layer0, n_layers, q);
     if (rc == XSV_OK) rc = do_quantize(ctx, layer0, n_layers, k, v);
     ctx->work = ctx->stream;
   }
-  if (fork) {  // join even after an error so the streams stay ordered
+  if (fork && ctx->overlap == 2) {
+    if (hipEventRecord(ctx->ev_chain[layer0], ctx->side) != hipSuccess) return hip_fail(ctx);
+    for (int l = layer0; l < layer0 + n_layers; ++l) ctx->pending[l] = layer0;
+  } else if (fork) {  // join even after an error so the streams stay ordered
     if (hipEventRecord(ctx->ev_join, ctx->side) != hipSuccess || hipStreamWaitEvent(ctx->stream, ctx->ev_join, 0) != hipSuccess)
       return hip_fail(ctx);
   }
@@ -476,9 +521,11 @@ int xsv_step_all_layers(xsv_ctx* ctx, const xsv_tensor* q, const xsv_tensor* k_n
   return step_layers(ctx, 0, L, q, k_new, v_new, out, ctx->splits_batched);
 }
 
-int xsv_set_overlap(xsv_ctx* ctx, int enabled) {
-  if (!ctx) return XSV_ERR_ARG;
-  ctx->overlap = enabled != 0;
+int xsv_set_overlap(xsv_ctx* ctx, int mode) {
+  if (!ctx || mode < 0 || mode > 2) return XSV_ERR_ARG;
+  const int rc = join_layers(ctx, 0, ctx->cfg.n_layers);
+  if (rc != XSV_OK) return rc;
+  ctx->overlap = mode;
   return XSV_OK;
 }
 
@@ -498,6 +545,7 @@ int xsv_cache_export(xsv_ctx* ctx, int layer, uint8_t* k_codes, float* k_scale, 
   if (rc != XSV_OK) return rc;
   const LayerState& L = ctx->layers[layer];
   if (L.phase != kIdle) return XSV_ERR_STATE;
+  if ((rc = join_layers(ctx, layer, 1)) != XSV_OK) return rc;
   const xsv_config& c = ctx->cfg;
   const bool quant = c.kv_bits != 16;
   if (!quant && (k_codes || k_scale || k_zero || v_codes || v_scale || v_zero)) return XSV_ERR_ARG;
@@ -553,6 +601,7 @@ int xsv_cache_import(xsv_ctx* ctx, int layer, int32_t T, int32_t frames_seen, co
   }
   const int H = c.n_heads, G = c.group_size, bits = c.kv_bits;
   const LayerCache lc = layer_cache(p, L.buf, layer);
+  if ((rc = join_layers(ctx, layer, 1)) != XSV_OK) return rc;
   if (hipStreamSynchronize(ctx->stream) != hipSuccess) return hip_fail(ctx);
   // pack on the host into the library's private layout (layout marshalling only)
   const size_t row_bytes = p.code_row_bytes();
@@ -608,6 +657,7 @@ int xsv_last_selection(xsv_ctx* ctx, int layer, int32_t* n_scores, float* scores
   int rc = check_layer(ctx, layer);
   if (rc != XSV_OK) return rc;
   const LayerState& L = ctx->layers[layer];
+  if ((rc = join_layers(ctx, layer, 1)) != XSV_OK) return rc;
   if (n_scores) *n_scores = L.last_P;
   if (n_keep) *n_keep = L.last_keep;
   bool good = true;

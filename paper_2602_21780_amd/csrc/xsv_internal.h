@@ -98,10 +98,20 @@ struct AttendArgs {
   CachePool pool;
   Batch b;
   Workspace ws;
-  int Tc, n, n_splits;
-  int variant;   // 0: 4 waves x 64 queries, 1: 4 waves x 32 queries, 2: 8 waves x 32 queries per workgroup
+  int Tc, n;
+  int variant;   // waves x query rows per wave of a workgroup: 0: 4 x 64, 1: 4 x 32, 2: 8 x 32, 3: 8 x 64
+  int n_wgs;     // workgroups the (unit, tile) line is cut into (from plan_attend)
+  int rows_wg;   // query rows per workgroup of this variant
+  int cut;       // some unit is shared by several workgroups: partials are written and merged
   float qscale;  // softmax scale * log2(e)
 };
+constexpr int kMaxPieces = 16;  // workgroups that may share one unit
+struct AttendPlan {
+  int n_wgs, rows_wg, max_pieces;
+};
+// Chooses the grid: at most want_wgs workgroups, pieces of at least 4 tiles, and no unit shared by
+// more workgroups than the partial workspace (part_rows rows) and the merge can hold.
+AttendPlan plan_attend(int variant, int n_layers, int H, int n, int Tc, int want_wgs, size_t part_rows);
 hipError_t launch_attend(const AttendArgs& a, hipStream_t stream);
 int attend_rows_per_workgroup(int variant);
 

@@ -42,7 +42,7 @@ class xsv_tensor(C.Structure):
 # every symbol include/xsv.h declares
 EXPORTS = (
     "xsv_create", "xsv_destroy", "xsv_reset", "xsv_dequant_attend", "xsv_score_prune", "xsv_quantize",
-    "xsv_step", "xsv_step_all_layers", "xsv_set_attend_splits", "xsv_set_attend_variant", "xsv_set_overlap", "xsv_cache_len", "xsv_cache_export",
+    "xsv_step", "xsv_step_all_layers", "xsv_set_attend_splits", "xsv_set_attend_variant", "xsv_set_overlap", "xsv_join", "xsv_set_side_cus", "xsv_cache_len", "xsv_cache_export",
     "xsv_cache_import", "xsv_last_selection", "xsv_quantize_k", "xsv_quantize_v", "xsv_score",
     "xsv_topk_keep", "xsv_strerror",
 )
@@ -63,6 +63,7 @@ def lib():
         L.xsv_create.argtypes = [C.POINTER(xsv_config), vp, C.POINTER(vp)]
         L.xsv_destroy.argtypes = [vp]
         L.xsv_reset.argtypes = [vp]
+        L.xsv_join.argtypes = [vp]
         L.xsv_dequant_attend.argtypes = [vp, i32, T, T, T, vp]
         L.xsv_score_prune.argtypes = [vp, i32, T]
         L.xsv_quantize.argtypes = [vp, i32, T, T]
@@ -71,6 +72,7 @@ def lib():
         L.xsv_set_attend_splits.argtypes = [vp, i32, i32]
         L.xsv_set_attend_variant.argtypes = [vp, i32]
         L.xsv_set_overlap.argtypes = [vp, i32]
+        L.xsv_set_side_cus.argtypes = [vp, i32]
         L.xsv_cache_len.argtypes = [vp, i32, C.POINTER(C.c_int32)]
         L.xsv_cache_export.argtypes = [vp, i32] + [vp] * 10
         L.xsv_cache_import.argtypes = [vp, i32, C.c_int32, C.c_int32] + [vp] * 10
@@ -169,8 +171,14 @@ class Context:
     def set_attend_variant(self, variant):
         _check(lib().xsv_set_attend_variant(self._h, variant), "xsv_set_attend_variant")
 
-    def set_overlap(self, enabled):
-        _check(lib().xsv_set_overlap(self._h, int(enabled)), "xsv_set_overlap")
+    def set_overlap(self, mode):
+        _check(lib().xsv_set_overlap(self._h, int(mode)), "xsv_set_overlap")
+
+    def join(self):
+        _check(lib().xsv_join(self._h), "xsv_join")
+
+    def set_side_cus(self, compute_units):
+        _check(lib().xsv_set_side_cus(self._h, int(compute_units)), "xsv_set_side_cus")
 
     def _out(self, q, out):
         if out is None:

@@ -65,6 +65,8 @@ def test_batched_all_layers_equals_per_layer_steps():
     spec = CONFIGS[0].with_(name="batched", n_layers=3, n_heads=4, tokens_per_frame=150, budget=400, group_size=64, seed=5)
     ctx_a = xsv.Context.from_spec(spec)
     ctx_b = xsv.Context.from_spec(spec)
+    for ctx in (ctx_a, ctx_b):
+        ctx.set_attend_splits(2, 2)   # the same key ranges in both launch forms: outputs equal to the bit
     src = FrameSource(spec, DEV)
     for f in range(5):
         q, k, v = src.frame(f)
@@ -75,6 +77,40 @@ def test_batched_all_layers_equals_per_layer_steps():
         for l in range(spec.n_layers):
             da, db = ctx_a.cache_export(l), ctx_b.cache_export(l)
             parity.compare_cache(da, db, True)
+    ctx_a.destroy()
+    ctx_b.destroy()
+
+
+@pytest.mark.parametrize("batched", [False, True])
+def test_deferred_join_gives_the_same_bytes_as_one_stream(batched):
+    """Overlap mode 2 (the chain's join deferred to the layer's next use) against mode 0 (one stream)."""
+    spec = CONFIGS[0].with_(name="deferred", n_layers=4, n_heads=4, tokens_per_frame=150, budget=400, group_size=64, seed=9)
+    ctx_a = xsv.Context.from_spec(spec)
+    ctx_b = xsv.Context.from_spec(spec)
+    ctx_a.set_overlap(0)
+    ctx_b.set_overlap(2)
+    for ctx in (ctx_a, ctx_b):
+        ctx.set_attend_splits(2, 2)
+    src = FrameSource(spec, DEV)
+    frames = [src.frame(f) for f in range(6)]     # inputs stay alive, as mode 2 requires
+    outs_a, outs_b = [], []
+    for f, (q, k, v) in enumerate(frames):
+        if batched:
+            outs_a.append(ctx_a.step_all_layers(q, k, v))
+            outs_b.append(ctx_b.step_all_layers(q, k, v))
+        else:
+            outs_a.append(torch.stack([ctx_a.step(l, q[l], k[l], v[l]) for l in range(spec.n_layers)]))
+            outs_b.append(torch.stack([ctx_b.step(l, q[l], k[l], v[l]) for l in range(spec.n_layers)]))
+        if f % 2:
+            ctx_b.join()                           # every other frame: an explicit join; else the next use joins
+    ctx_b.join()
+    torch.cuda.synchronize()
+    for a, b in zip(outs_a, outs_b):
+        assert torch.equal(a, b)
+    for l in range(spec.n_layers):
+        parity.compare_cache(ctx_a.cache_export(l), ctx_b.cache_export(l), True)
+        sa, sb = ctx_a.last_selection(l), ctx_b.last_selection(l)
+        assert np.array_equal(sa[0], sb[0]) and np.array_equal(sa[1], sb[1])
     ctx_a.destroy()
     ctx_b.destroy()
 
