@@ -46,7 +46,9 @@ def main():
     ap.add_argument("--mode", choices=["layerwise", "batched"], default="layerwise")
     ap.add_argument("--splits", type=int, default=0, help="key ranges per attention launch (0 = auto)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
-    ap.add_argument("--no-overlap", action="store_true", help="run the prune chain after attention on one stream")
+    ap.add_argument("--overlap", type=int, choices=[0, 1, 2], default=2,
+                    help="0: prune chain after attention on one stream; 1: on a side stream, joined per call; "
+                         "2: side stream, joined lazily (once per frame here)")
     ap.add_argument("--side-cus", type=int, default=-1, help="compute units left to the overlapped prune chain (-1 = library default)")
     ap.add_argument("--stage-frames", type=int, default=6, help="frames of the per-stage event-timed pass")
     args = ap.parse_args()
@@ -74,8 +76,7 @@ def main():
     out = torch.empty((L, spec.n_heads, n, spec.head_dim), dtype=torch.bfloat16, device=dev)
     ctx = xsv.Context.from_spec(spec)
     ctx.set_attend_splits(args.splits, args.splits)
-    if args.no_overlap:
-        ctx.set_overlap(False)
+    ctx.set_overlap(args.overlap)
     if args.side_cus >= 0:
         ctx.set_side_cus(args.side_cus)
     packed = [ctx.pack_layers(q, k, v, out) for (q, k, v) in frames]
@@ -88,6 +89,7 @@ def main():
             q, k, v = frames[f]
             for l in range(L):
                 ctx.step(l, q[l], k[l], v[l], out[l])
+        ctx.join()   # the frame's last re-quantization is ordered before whatever follows on the stream
 
     def timed(mode, f0, count):
         torch.cuda.synchronize()
@@ -111,28 +113,32 @@ def main():
         run_frame(f, other)
     other_fps = K / timed(other, W, K)
 
-    # ---- per-stage durations with events on the launch stream (steady state, layer by layer) ---------
+    # ---- per-stage durations with events on the launch stream (steady state) --------------------------
+    # Each stage is launched for all 24 layers back to back between two events (the layers are
+    # independent of each other), so one event pair brackets 24 launches and its own cost is amortized.
+    ctx.join()
     ev = lambda: torch.cuda.Event(enable_timing=True)
     stage_ms = {"attend": 0.0, "score_prune": 0.0, "quantize": 0.0}
-    count = 0
+    marks = []
     for f in range(W + K, W + K + S):
         q, k, v = frames[f]
-        marks = []
+        e = [ev() for _ in range(4)]
+        e[0].record()
         for l in range(L):
-            e = [ev() for _ in range(4)]
-            e[0].record(); ctx.dequant_attend(l, q[l], k[l], v[l], out[l])
-            e[1].record(); ctx.score_prune(l, q[l])
-            e[2].record(); ctx.quantize(l, k[l], v[l])
-            e[3].record()
-            marks.append(e)
-        torch.cuda.synchronize()
-        for e in marks:
-            stage_ms["attend"] += e[0].elapsed_time(e[1])
-            stage_ms["score_prune"] += e[1].elapsed_time(e[2])
-            stage_ms["quantize"] += e[2].elapsed_time(e[3])
-            count += 1
-    for key in stage_ms:
-        stage_ms[key] /= count
+            ctx.dequant_attend(l, q[l], k[l], v[l], out[l])
+        e[1].record()
+        for l in range(L):
+            ctx.score_prune(l, q[l])
+        e[2].record()
+        for l in range(L):
+            ctx.quantize(l, k[l], v[l])
+        e[3].record()
+        marks.append(e)
+    torch.cuda.synchronize()
+    for e in marks:
+        stage_ms["attend"] += e[0].elapsed_time(e[1]) / (L * len(marks))
+        stage_ms["score_prune"] += e[1].elapsed_time(e[2]) / (L * len(marks))
+        stage_ms["quantize"] += e[2].elapsed_time(e[3]) / (L * len(marks))
     Tn = ctx.cache_len(0)
     P = Tc + n - 2 * n
     work = algorithmic_work(spec, Tc, Tn, P)
@@ -191,7 +197,7 @@ def main():
         "config": {"workload": spec.name, "layers": L, "heads": spec.n_heads, "head_dim": spec.head_dim,
                    "tokens_per_frame": n, "budget": spec.budget, "kv_bits": spec.kv_bits, "group_size": spec.group_size,
                    "cache_tokens": Tc, "keys_per_step": Tc + n, "launch_form": args.mode,
-                   "attend_key_splits": args.splits or "auto"},
+                   "attend_key_splits": args.splits or "auto", "overlap_mode": args.overlap},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "other_launch_form": {"form": other, "frames_per_s": round(other_fps, 2)},

@@ -57,7 +57,10 @@ __device__ __forceinline__ int tau(int i) {
 template <int BITS>
 __device__ __forceinline__ void unpack_codes(uint32_t w, float* out) {
   if constexpr (BITS == 4) {
-    const uint32_t t0 = w & 0x0f0f0f0fu, t1 = (w >> 4) & 0x0f0f0f0fu;
+    uint32_t t0 = w & 0x0f0f0f0fu, t1 = (w >> 4) & 0x0f0f0f0fu;
+    // (opaque to the optimizer, which would otherwise fold the masks into one bit-field extract
+    // PER code in front of each conversion instead of the byte-select conversions below)
+    asm volatile("" : "+v"(t0), "+v"(t1));
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
       out[2 * b] = (float)((t0 >> (8 * b)) & 0xffu);  // v_cvt_f32_ubyte<b>
@@ -66,7 +69,8 @@ __device__ __forceinline__ void unpack_codes(uint32_t w, float* out) {
   } else {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const uint32_t t = (w >> (2 * i)) & 0x03030303u;
+      uint32_t t = (w >> (2 * i)) & 0x03030303u;
+      asm volatile("" : "+v"(t));
 #pragma unroll
       for (int b = 0; b < 4; ++b) out[4 * b + i] = (float)((t >> (8 * b)) & 0xffu);
     }
@@ -152,6 +156,16 @@ template <int BITS, int G, int NH>
 __device__ __forceinline__ void store_cache_tile(const Stage<BITS, G, NH>& st, uint16_t* lds, int u) {
   using S = Stage<BITS, G, NH>;
   const int r0 = u / S::kRI, o = u % S::kRI;
+  // (code - zero) * scale as one fused multiply-add per element: code * scale + (-zero * scale).
+  // It differs from the cache's canonical two-step value by at most one fp32 rounding of
+  // zero * scale, far below the bf16 rounding that follows.
+  float nzs[S::kQuant ? S::kSets : 1][S::kPer];
+  if constexpr (S::kQuant) {
+#pragma unroll
+    for (int set = 0; set < S::kSets; ++set)
+#pragma unroll
+      for (int e = 0; e < S::kPer; ++e) nzs[set][e] = -st.pz[set][e] * st.ps[set][e];
+  }
 #pragma unroll
   for (int it = 0; it < S::kIter; ++it) {
     uint16_t* dst = lds + (r0 + it * S::kRowStep) * kLdsStride + o * S::kPer;
@@ -163,8 +177,9 @@ __device__ __forceinline__ void store_cache_tile(const Stage<BITS, G, NH>& st, u
       unpack_codes<BITS>(st.code[it], f);
       uint32_t pk[S::kPer / 2];
 #pragma unroll
-      for (int e = 0; e < S::kPer; e += 2)  // the cache's view of an element: (code - zero) * scale, then bf16
-        pk[e / 2] = pack_bf16((f[e] - st.pz[set][e]) * st.ps[set][e], (f[e + 1] - st.pz[set][e + 1]) * st.ps[set][e + 1]);
+      for (int e = 0; e < S::kPer; e += 2)
+        pk[e / 2] = pack_bf16(__builtin_fmaf(f[e], st.ps[set][e], nzs[set][e]),
+                              __builtin_fmaf(f[e + 1], st.ps[set][e + 1], nzs[set][e + 1]));
 #pragma unroll
       for (int w = 0; w < S::kPer / 8; ++w)
         *reinterpret_cast<uint4*>(dst + w * 8) = make_uint4(pk[4 * w], pk[4 * w + 1], pk[4 * w + 2], pk[4 * w + 3]);

@@ -145,7 +145,10 @@ AttendPlan choose_grid(const xsv_ctx* ctx, int n_layers, int Tc, int requested, 
   const int rows = attend_rows_per_workgroup(ctx->attend_variant);
   const int n_units = ((c.tokens_per_frame + rows - 1) / rows) * c.n_heads * n_layers;
   const int per_cu = ctx->attend_variant >= 2 ? 1 : 2;
-  const int want = requested > 0 ? n_units * requested : per_cu * std::max(ctx->n_cu / 2, ctx->n_cu - spare_cus);
+  int want = requested > 0 ? n_units * requested : per_cu * std::max(ctx->n_cu / 2, ctx->n_cu - spare_cus);
+  // a grid that cuts every unit into the same number of ranges has no workgroup that ends one unit
+  // and begins another (two pipeline fills, two sets of partials); prefer it when it is nearly as large
+  if (requested <= 0 && want / n_units >= 1 && (want / n_units) * n_units * 8 >= want * 7) want = (want / n_units) * n_units;
   return plan_attend(ctx->attend_variant, n_layers, c.n_heads, c.tokens_per_frame, Tc, want, ctx->part_rows);
 }
 
