@@ -61,6 +61,32 @@ def test_unbounded_bf16_cache_matches_brute_force_attention():
     run_stream(spec, 5)
 
 
+@pytest.mark.parametrize("rising", [True, False])
+@pytest.mark.parametrize("bits,splits", [(16, 1), (4, 1), (4, 3)])
+def test_logits_that_drift_far_along_the_key_axis(rising, bits, splits):
+    """Logits that rise (or fall) by hundreds of powers of two from the oldest cached token to the
+    current frame: the softmax reference taken from the first keys of a range must move (rising), or
+    everything after it must underflow harmlessly (falling)."""
+    spec = CONFIGS[0].with_(name="drift", n_heads=2, tokens_per_frame=96, budget=0, kv_bits=bits, group_size=64,
+                            n_layers=1, seed=3)
+    ctx, st = parity.make_pair(spec, max_frames=6)
+    ctx.set_attend_splits(splits, splits)
+    g = torch.Generator(device="cpu").manual_seed(7)
+    sign = (torch.randint(0, 2, (spec.head_dim,), generator=g) * 2 - 1).float()
+    worst = 0.0
+    for f in range(5):
+        level = (f + 1) if rising else (5 - f)
+        # q.k = 64 * 4 * 2.5 * level = 640 * level: 115 powers of two per frame after the 1/8 scale
+        q = (4.0 * sign + 0.25 * torch.randn(spec.n_heads, 96, 64, generator=g)).to(torch.bfloat16).to(DEV)
+        k = (2.5 * level * sign + 0.25 * torch.randn(spec.n_heads, 96, 64, generator=g)).to(torch.bfloat16).to(DEV)
+        v = torch.randn(spec.n_heads, 96, 64, generator=g).to(torch.bfloat16).to(DEV)
+        print(f"  drift frame {f} level {level} T={ctx.cache_len(0)}", flush=True)
+        (ma, rr), _ = parity.step_and_compare(ctx, st, spec, 0, 0, q, k, v, budget=0)
+        worst = max(worst, ma)
+    print(f"  worst max_abs={worst:.3e}", flush=True)
+    ctx.destroy()
+
+
 def test_batched_all_layers_equals_per_layer_steps():
     spec = CONFIGS[0].with_(name="batched", n_layers=3, n_heads=4, tokens_per_frame=150, budget=400, group_size=64, seed=5)
     ctx_a = xsv.Context.from_spec(spec)
