@@ -46,10 +46,14 @@ def main():
     ap.add_argument("--mode", choices=["layerwise", "batched"], default="layerwise")
     ap.add_argument("--splits", type=int, default=0, help="key ranges per attention launch (0 = auto)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--both-forms", action="store_true", help="also time the other launch form (extra kernels in a profile)")
     ap.add_argument("--overlap", type=int, choices=[0, 1, 2], default=2,
                     help="0: prune chain after attention on one stream; 1: on a side stream, joined per call; "
                          "2: side stream, joined lazily (once per frame here)")
     ap.add_argument("--side-cus", type=int, default=-1, help="compute units left to the overlapped prune chain (-1 = library default)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain streaming kernel of known size (1 GiB read + 1 GiB written, 4 times), the yardstick "
+                         "for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--stage-frames", type=int, default=6, help="frames of the per-stage event-timed pass")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -106,17 +110,27 @@ def main():
     ms_per_step = elapsed / K * 1e3
     value = K / elapsed
 
-    # the other launch form on the same frames, for context
-    other = "batched" if args.mode == "layerwise" else "layerwise"
-    ctx.reset()
-    for f in range(W):
-        run_frame(f, other)
-    other_fps = K / timed(other, W, K)
+    step_wgs = ctx.last_attend_workgroups()   # attention grid of the timed steps
+
+    # the other launch form on the same frames, for context (off by default: it launches the same
+    # kernels in other shapes, which would blur a per-kernel profile of this command)
+    other, other_fps = ("batched" if args.mode == "layerwise" else "layerwise"), None
+    if args.both_forms:
+        ctx.reset()
+        for f in range(W):
+            run_frame(f, other)
+        other_fps = K / timed(other, W, K)
+        ctx.reset()
+        for f in range(W):
+            run_frame(f, args.mode)
 
     # ---- per-stage durations with events on the launch stream (steady state) --------------------------
     # Each stage is launched for all 24 layers back to back between two events (the layers are
     # independent of each other), so one event pair brackets 24 launches and its own cost is amortized.
     ctx.join()
+    n_units = spec.n_heads * ((n + 511) // 512)
+    if args.splits == 0 and step_wgs % n_units == 0:
+        ctx.set_attend_splits(step_wgs // n_units, 0)   # the grid the timed steps used (they leave units to the chain)
     ev = lambda: torch.cuda.Event(enable_timing=True)
     stage_ms = {"attend": 0.0, "score_prune": 0.0, "quantize": 0.0}
     marks = []
@@ -148,6 +162,7 @@ def main():
         "bound": "mfma", "achieved": round(attend_tflops, 2), "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
         "frac": round(attend_tflops / PEAK_BF16_MFMA_TFLOPS, 4), "traffic": None,
         "flop_per_launch": work["attend_flop"], "avg_launch_ms": round(stage_ms["attend"], 4),
+        "workgroups": ctx.last_attend_workgroups(),
     }
     hbm = {
         "score_prune_GBs": round(work["score_bytes"] / (stage_ms["score_prune"] * 1e-3) / 1e9, 1),
@@ -200,11 +215,17 @@ def main():
                    "attend_key_splits": args.splits or "auto", "overlap_mode": args.overlap},
         "roofline": roofline,
         "cpu_baseline": cpu,
-        "other_launch_form": {"form": other, "frames_per_s": round(other_fps, 2)},
+        "other_launch_form": {"form": other, "frames_per_s": round(other_fps, 2)} if other_fps else None,
         "attention_TFLOPs_whole_step": round(work["attend_flop"] * L * value / 1e12, 2),
         "hbm_stages": hbm,
     }
     ctx.destroy()
+    if args.calibrate_copy:
+        src_t = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB
+        dst_t = torch.empty_like(src_t)
+        for _ in range(4):
+            torch.mul(src_t, 2.0, out=dst_t)                                # one elementwise kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
     print(json.dumps(result))
 
 

@@ -137,6 +137,8 @@ int xsv_join(xsv_ctx* ctx);
  * overlapped score/select/re-quantize chain (default 64; 0 .. half the chip).  Without spare units
  * the chain only starts when attention drains.  Ignored when overlap is off or splits are fixed. */
 int xsv_set_side_cus(xsv_ctx* ctx, int compute_units);
+/* Grid (workgroups) of the most recent attention launch of this context, 0 before the first. */
+int xsv_last_attend_workgroups(xsv_ctx* ctx, int32_t* workgroups);
 /* Tuning: workgroup shape of the attention kernel (waves x query rows per wave).  3 (default) = 8 x 64,
  * 0 = 4 x 64, 1 = 4 x 32, 2 = 8 x 32.  Other values: XSV_ERR_ARG.  Results agree to rounding. */
 int xsv_set_attend_variant(xsv_ctx* ctx, int variant);

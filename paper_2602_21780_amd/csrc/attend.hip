@@ -46,6 +46,12 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+__device__ __forceinline__ uint32_t pack_f16(float a, float b) {
+  const f32x2 v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
+}
+
 // Row of the K tile that MFMA row i of S^T reads, so that accumulator register r of the lane
 // half hh holds token 16*(r/8) + 8*hh + r%8 — the order in which the PV product consumes tokens.
 __device__ __forceinline__ int tau(int i) {
@@ -274,9 +280,19 @@ __device__ __forceinline__ MfmaHook<N, F> with_mfma(F f) { return MfmaHook<N, F>
 struct Partition {
   long long total;  // n_units * n_tiles
   int n_tiles, n_wgs;
-  __host__ __device__ long long begin(int w) const { return total * w / n_wgs; }
+  // 64-bit division is a long instruction sequence on this target; launches of realistic size fit 32 bits
+  __host__ __device__ bool small() const { return total * (n_wgs + 1) < (1ll << 31); }
+  __host__ __device__ long long begin(int w) const {
+    return small() ? (long long)((unsigned)total * (unsigned)w / (unsigned)n_wgs) : total * w / n_wgs;
+  }
   // workgroup whose piece holds item x
-  __host__ __device__ int owner(long long x) const { return (int)(((x + 1) * n_wgs + total - 1) / total) - 1; }
+  __host__ __device__ int owner(long long x) const {
+    return small() ? (int)((((unsigned)x + 1u) * (unsigned)n_wgs + (unsigned)total - 1u) / (unsigned)total) - 1
+                   : (int)(((x + 1) * n_wgs + total - 1) / total) - 1;
+  }
+  __host__ __device__ int unit_of(long long x) const {
+    return small() ? (int)((unsigned)x / (unsigned)n_tiles) : (int)(x / n_tiles);
+  }
   __host__ __device__ int first_wg(int unit) const { return owner((long long)unit * n_tiles); }
   __host__ __device__ int last_wg(int unit) const { return owner((long long)(unit + 1) * n_tiles - 1); }
 };
@@ -305,7 +321,7 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
   const long long piece_end = part.begin(blockIdx.x + 1);
 
   for (long long pos = part.begin(blockIdx.x); pos < piece_end;) {
-  const int unit = (int)(pos / part.n_tiles);
+  const int unit = part.unit_of(pos);
   const int t_begin = (int)(pos - (long long)unit * part.n_tiles);
   const int t_end = (int)min((long long)part.n_tiles, t_begin + (piece_end - pos));
   pos += t_end - t_begin;
@@ -537,7 +553,7 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
   for (int cb = 0; cb < QB; ++cb) {
     const int q_row = q_row0 + 32 * cb + j;
     const float lsum = l[cb] + __shfl_xor(l[cb], 32);  // the two lane halves saw disjoint tokens
-    if (q_row >= n) continue;
+    if (q_row >= n) continue;  // (both lanes of a row leave together, so the lane exchange below stays paired)
     if (whole) {
       const float inv = 1.0f / lsum;
       uint16_t* op = a.b.out[lb] + ((size_t)h * n + q_row) * kD;
@@ -550,16 +566,28 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
                                                             pack_bf16(o1[cb][4 * q4 + 2] * inv, o1[cb][4 * q4 + 3] * inv));
       }
     } else {
+      // Partial of a cut unit, as fp16 mantissas under one power-of-two scale per query row (the
+      // row's largest magnitude maps into [0.5, 1): 11 bits below the row maximum, half the bytes of
+      // fp32).  Lane (j, hh) owns 32 channels of row j and writes them as one 64-byte run, in
+      // register order: o0[0..15], o1[0..15].
       const int piece = (int)blockIdx.x - part.first_wg(unit);
       const size_t row = (((size_t)piece * a.b.n_layers + lb) * H + h) * n + q_row;
-      float* op = a.ws.attn_o + row * kD;
+      float amax = 0.f;
 #pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        const int c = 8 * q4 + 4 * hh;
-        *reinterpret_cast<float4*>(op + c) = make_float4(o0[cb][4 * q4], o0[cb][4 * q4 + 1], o0[cb][4 * q4 + 2], o0[cb][4 * q4 + 3]);
-        *reinterpret_cast<float4*>(op + 32 + c) = make_float4(o1[cb][4 * q4], o1[cb][4 * q4 + 1], o1[cb][4 * q4 + 2], o1[cb][4 * q4 + 3]);
+      for (int r = 0; r < 16; ++r) amax = fmaxf(amax, fmaxf(fabsf(o0[cb][r]), fabsf(o1[cb][r])));
+      amax = xhalf_max(amax);
+      const int e = __builtin_amdgcn_frexp_expf(amax);  // amax = f * 2^e, f in [0.5, 1)  (0 for amax == 0)
+      uint32_t hw[16];
+#pragma unroll
+      for (int r = 0; r < 16; r += 2) {
+        hw[r >> 1] = pack_f16(__builtin_amdgcn_ldexpf(o0[cb][r], -e), __builtin_amdgcn_ldexpf(o0[cb][r + 1], -e));
+        hw[8 + (r >> 1)] = pack_f16(__builtin_amdgcn_ldexpf(o1[cb][r], -e), __builtin_amdgcn_ldexpf(o1[cb][r + 1], -e));
       }
-      if (hh == 0) *reinterpret_cast<float2*>(a.ws.attn_ml + row * 2) = make_float2(m[cb] * c2, lsum);
+      uint4* op = reinterpret_cast<uint4*>(a.ws.attn_o + (row * 2 + hh) * 32);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) op[i] = make_uint4(hw[4 * i], hw[4 * i + 1], hw[4 * i + 2], hw[4 * i + 3]);
+      if (hh == 0)
+        *reinterpret_cast<float4*>(a.ws.attn_ml + row * 4) = make_float4(m[cb] * c2, lsum, __builtin_amdgcn_ldexpf(1.0f, e), 0.f);
     }
   }
   }  // units of this workgroup's piece
@@ -569,42 +597,60 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
 // Merge of the pieces of every unit that was cut:  out = sum_p 2^(m_p - M) O_p / sum_p 2^(m_p - M) l_p.
 // (A separate launch on purpose: a device-wide release/acquire inside the attention kernel costs an
 // L2 write-back per workgroup on this multi-die part, far more than a second small kernel.)
+// Grid: x = boundary between workgroups w-1 | w of the attention grid (w = blockIdx.x + 1), y = chunk
+// of 32 query rows of the unit that boundary falls into.  A unit with several boundaries is handled
+// at its first one; a boundary that coincides with a unit's edge has nothing to merge.
+// Thread = (row, lane half hh, quarter of the lane's 32 values): 8 fp16 values of every piece.
 __global__ __launch_bounds__(256) void combine_kernel(const AttendArgs a) {
   const int H = a.pool.H, n = a.n;
-  const size_t rows = (size_t)a.b.n_layers * H * n;
-  const size_t gid = (size_t)blockIdx.x * 256 + threadIdx.x;
-  const size_t row = gid >> 4;
-  const int c = (int)(gid & 15) * 4;
-  if (row >= rows) return;
-  const int lb = (int)(row / ((size_t)H * n));
-  const size_t in_layer = row - (size_t)lb * H * n;
-  const int h = (int)(in_layer / n), q_row = (int)(in_layer - (size_t)h * n);
   const int nqb = (n + a.rows_wg - 1) / a.rows_wg;
   const int n_tiles = (a.Tc + kTile - 1) / kTile + (n + kTile - 1) / kTile;
   const Partition part{(long long)a.b.n_layers * H * nqb * n_tiles, n_tiles, a.n_wgs};
-  const int unit = (lb * H + h) * nqb + q_row / a.rows_wg;
-  const int S = part.last_wg(unit) - part.first_wg(unit) + 1;
-  if (S == 1) return;  // written by the attention kernel itself
-  float ms[kMaxPieces], ls[kMaxPieces];
+  const int w = blockIdx.x + 1;
+  const long long pos = part.begin(w);
+  const int unit = part.unit_of(pos);
+  if (pos == (long long)unit * n_tiles) return;
+  const int w0 = part.first_wg(unit);
+  if (w0 + 1 != w) return;
+  const int S = part.last_wg(unit) - w0 + 1;
+  const int qb = unit % nqb, h = (unit / nqb) % H, lb = unit / (nqb * H);
+  const int tid = threadIdx.x;
+  const int q_row = qb * a.rows_wg + 32 * blockIdx.y + (tid >> 3);
+  const int hh = (tid >> 2) & 1, qd = tid & 3;
+  if (q_row >= n) return;
+  const size_t rows = (size_t)a.b.n_layers * H * n;
+  const size_t row = ((size_t)lb * H + h) * n + q_row;
+  float ms[kMaxPieces], ls[kMaxPieces], sc[kMaxPieces];
   float M = kNegBig;
 #pragma unroll 4
   for (int s = 0; s < S; ++s) {
-    const float2 ml = *reinterpret_cast<const float2*>(a.ws.attn_ml + (s * rows + row) * 2);
+    const float4 ml = *reinterpret_cast<const float4*>(a.ws.attn_ml + (s * rows + row) * 4);
     ms[s] = ml.x;
     ls[s] = ml.y;
+    sc[s] = ml.z;
     M = fmaxf(M, ml.x);
   }
-  float L = 0.f, acc[4] = {0.f, 0.f, 0.f, 0.f};
+  float L = 0.f, acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll 4
   for (int s = 0; s < S; ++s) {
-    const float w = __builtin_amdgcn_exp2f(ms[s] - M);
-    const float4 o = *reinterpret_cast<const float4*>(a.ws.attn_o + (s * rows + row) * kD + c);
-    L += w * ls[s];
-    acc[0] += w * o.x; acc[1] += w * o.y; acc[2] += w * o.z; acc[3] += w * o.w;
+    const float wgt = __builtin_amdgcn_exp2f(ms[s] - M);
+    const uint4 o = *reinterpret_cast<const uint4*>(a.ws.attn_o + ((s * rows + row) * 2 + hh) * 32 + 8 * qd);
+    L += wgt * ls[s];
+    const float ws = wgt * sc[s];
+    const uint32_t ow[4] = {o.x, o.y, o.z, o.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const f16x2 v = __builtin_bit_cast(f16x2, ow[i]);
+      acc[2 * i] += ws * (float)v[0];
+      acc[2 * i + 1] += ws * (float)v[1];
+    }
   }
   const float inv = 1.0f / L;
-  *reinterpret_cast<uint2*>(a.b.out[lb] + in_layer * kD + c) =
-      make_uint2(pack_bf16(acc[0] * inv, acc[1] * inv), pack_bf16(acc[2] * inv, acc[3] * inv));
+  // values 8*qd + t of the lane: accumulator registers r = 8*(qd%2) + t of o0 (qd < 2) or o1, i.e.
+  // channels 32*(qd/2) + 16*(qd%2) + {0, 8} + 4*hh + 0..3
+  uint16_t* op = a.b.out[lb] + ((size_t)h * n + q_row) * kD + 32 * (qd >> 1) + 16 * (qd & 1) + 4 * hh;
+  *reinterpret_cast<uint2*>(op) = make_uint2(pack_bf16(acc[0] * inv, acc[1] * inv), pack_bf16(acc[2] * inv, acc[3] * inv));
+  *reinterpret_cast<uint2*>(op + 8) = make_uint2(pack_bf16(acc[4] * inv, acc[5] * inv), pack_bf16(acc[6] * inv, acc[7] * inv));
 }
 
 template <int BITS, int G, int NW, int QB>
@@ -613,8 +659,7 @@ static hipError_t launch_attend_t(const AttendArgs& a, hipStream_t stream) {
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (a.cut) {
-    const size_t threads = (size_t)a.b.n_layers * a.pool.H * a.n * 16;
-    hipLaunchKernelGGL(combine_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream, a);
+    hipLaunchKernelGGL(combine_kernel, dim3(a.n_wgs - 1, (a.rows_wg + 31) / 32), dim3(256), 0, stream, a);
     e = hipGetLastError();
   }
   return e;

@@ -50,6 +50,7 @@ struct xsv_ctx {
   std::vector<void*> allocs;
   int splits_single = 0, splits_batched = 0;
   int attend_variant = 3;  // 8 waves x 64 query rows per workgroup
+  int last_attend_wgs = 0;  // grid of the most recent attention launch
   int side_cus = 64;  // compute units xsv_step leaves to the prune chain while attention runs
   size_t part_rows = 0;  // rows the partial-output workspace holds
   int n_cu = 256;
@@ -197,6 +198,7 @@ int do_attend(xsv_ctx* ctx, int layer0, int n_layers, const xsv_tensor* q, const
   a.n_wgs = plan.n_wgs;
   a.rows_wg = plan.rows_wg;
   a.cut = plan.max_pieces > 1;
+  ctx->last_attend_wgs = plan.n_wgs;
   a.qscale = ctx->cfg.softmax_scale * 1.4426950408889634f;
   if (launch_attend(a, ctx->stream) != hipSuccess) return hip_fail(ctx);
   for (int i = 0; i < n_layers; ++i) ctx->layers[layer0 + i].phase = kAttended;
@@ -390,7 +392,7 @@ int xsv_create(const xsv_config* cfg, void* hip_stream, xsv_ctx** out) {
   const size_t part_rows = (size_t)std::max(16, 2 * std::min(c.n_layers, kMaxBatch)) * c.n_heads * n;
   ctx->part_rows = part_rows;
   A(&w.attn_o, part_rows * kD, false);
-  A(&w.attn_ml, part_rows * 2, false);
+  A(&w.attn_ml, part_rows * 4, false);
   if (rc == XSV_OK && hipStreamSynchronize(ctx->stream) != hipSuccess) rc = XSV_ERR_HIP;
   if (rc != XSV_OK) {
     free_all(ctx);
@@ -429,6 +431,12 @@ int xsv_set_attend_splits(xsv_ctx* ctx, int per_layer_calls, int batched_calls) 
   if (!ctx || per_layer_calls < 0 || per_layer_calls > 16 || batched_calls < 0 || batched_calls > 16) return XSV_ERR_ARG;
   ctx->splits_single = per_layer_calls;
   ctx->splits_batched = batched_calls;
+  return XSV_OK;
+}
+
+int xsv_last_attend_workgroups(xsv_ctx* ctx, int32_t* workgroups) {
+  if (!ctx || !workgroups) return XSV_ERR_ARG;
+  *workgroups = ctx->last_attend_wgs;
   return XSV_OK;
 }
 

@@ -86,8 +86,8 @@ struct Workspace {
   float* scores;      // [L][Tcap + n]      importance of the middle tokens
   int32_t* keep;      // [L][Tcap + n]      keep list
   float* qpart;       // [L][qpart_rows][64] partial weighted query sums
-  float* attn_o;      // [splits][batch layers][H][n][64] unnormalized partial outputs
-  float* attn_ml;     // [splits][batch layers][H][n][2]  running max (log2 domain), row sum
+  uint16_t* attn_o;   // [pieces][batch layers][H][n][2][32] fp16 mantissas of the unnormalized partial outputs
+  float* attn_ml;     // [pieces][batch layers][H][n][4]  softmax reference (log2 domain), row sum, row scale, -
   int scores_stride;  // Tcap + n
   int qpart_rows;
 };

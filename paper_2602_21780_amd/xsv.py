@@ -42,7 +42,7 @@ class xsv_tensor(C.Structure):
 # every symbol include/xsv.h declares
 EXPORTS = (
     "xsv_create", "xsv_destroy", "xsv_reset", "xsv_dequant_attend", "xsv_score_prune", "xsv_quantize",
-    "xsv_step", "xsv_step_all_layers", "xsv_set_attend_splits", "xsv_set_attend_variant", "xsv_set_overlap", "xsv_join", "xsv_set_side_cus", "xsv_cache_len", "xsv_cache_export",
+    "xsv_step", "xsv_step_all_layers", "xsv_set_attend_splits", "xsv_set_attend_variant", "xsv_set_overlap", "xsv_join", "xsv_set_side_cus", "xsv_last_attend_workgroups", "xsv_cache_len", "xsv_cache_export",
     "xsv_cache_import", "xsv_last_selection", "xsv_quantize_k", "xsv_quantize_v", "xsv_score",
     "xsv_topk_keep", "xsv_strerror",
 )
@@ -73,6 +73,7 @@ def lib():
         L.xsv_set_attend_variant.argtypes = [vp, i32]
         L.xsv_set_overlap.argtypes = [vp, i32]
         L.xsv_set_side_cus.argtypes = [vp, i32]
+        L.xsv_last_attend_workgroups.argtypes = [vp, C.POINTER(C.c_int32)]
         L.xsv_cache_len.argtypes = [vp, i32, C.POINTER(C.c_int32)]
         L.xsv_cache_export.argtypes = [vp, i32] + [vp] * 10
         L.xsv_cache_import.argtypes = [vp, i32, C.c_int32, C.c_int32] + [vp] * 10
@@ -173,6 +174,11 @@ class Context:
 
     def set_overlap(self, mode):
         _check(lib().xsv_set_overlap(self._h, int(mode)), "xsv_set_overlap")
+
+    def last_attend_workgroups(self) -> int:
+        w = C.c_int32()
+        _check(lib().xsv_last_attend_workgroups(self._h, C.byref(w)), "xsv_last_attend_workgroups")
+        return w.value
 
     def join(self):
         _check(lib().xsv_join(self._h), "xsv_join")
