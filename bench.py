@@ -23,6 +23,10 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X dense bf16
 PEAK_HBM_GBS = 8000.0
+# HBM bytes of one attend_kernel launch of this workload (fetch 35.6 MB + write 20.1 MB), from the two
+# rocprofv3 --pmc runs summarized in profiles/attend_cfg2_hbm_traffic.md; not measurable from inside this
+# process, so it is carried here and only reported for the grid it was measured on.
+TRAFFIC_ATTEND_CFG2 = {"workgroups": 192, "bytes": 55.8e6}
 
 
 def algorithmic_work(spec, Tc, Tn, P):
@@ -160,7 +164,10 @@ def main():
     roofline = {
         "kernel": "attend_kernel<4,64> (+ combine_kernel when key ranges are split)",
         "bound": "mfma", "achieved": round(attend_tflops, 2), "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
-        "frac": round(attend_tflops / PEAK_BF16_MFMA_TFLOPS, 4), "traffic": None,
+        "frac": round(attend_tflops / PEAK_BF16_MFMA_TFLOPS, 4),
+        "traffic": TRAFFIC_ATTEND_CFG2["bytes"] if ctx.last_attend_workgroups() == TRAFFIC_ATTEND_CFG2["workgroups"] else None,
+        "traffic_unit": "bytes per attend_kernel launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, profiles/attend_cfg2_hbm_traffic.md)",
+        "algorithmic_bytes": work["attend_bytes"],
         "flop_per_launch": work["attend_flop"], "avg_launch_ms": round(stage_ms["attend"], 4),
         "workgroups": ctx.last_attend_workgroups(),
     }
