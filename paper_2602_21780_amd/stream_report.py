@@ -1,0 +1,94 @@
+#!/usr/bin/env python3
+"""Secondary measurements of the streaming step (one GPU): the other workload shapes, and the constant-cost
+claim of the method against an uncompressed cache (paper Sec. 3.2: once the budget is reached, memory and
+per-frame cost stay constant; Sec. 4.4 reports the same comparison on video streams).
+
+    python -m paper_2602_21780_amd.stream_report --configs 0,1,2,4
+    python -m paper_2602_21780_amd.stream_report --long 200
+
+`--configs`: frames/s of each listed workload at its saturated cache, layer by layer through xsv_step
+(overlap mode 2, one xsv_join per frame), events on the launch stream around each frame's 24 (or 1) steps.
+`--long N`: the 24-layer drifting stream for N frames, once with the 4-bit budgeted cache and once with an
+unbounded bf16 cache (kv_bits 16, budget 0); prints ms/frame and cache bytes at checkpoints.
+Inputs are synthetic (seeded), generated on the device outside the timed regions.  One JSON line per row.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+
+sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+
+
+def cache_bytes(spec, T):
+    D = spec.n_heads * spec.head_dim
+    per = 2.0 if spec.kv_bits == 16 else spec.kv_bits / 8.0 + 8.0 / spec.group_size
+    return 2 * T * D * per * spec.n_layers
+
+
+def run_stream(spec, frames, checkpoints, torch, xsv, FrameSource, window=5):
+    """Steps `frames` frames; returns rows (frame, ms/frame averaged over the `window` frames ending there)."""
+    dev = "cuda:0"
+    L, n = spec.n_layers, spec.tokens_per_frame
+    ctx = xsv.Context.from_spec(spec, max_frames=frames + 1)
+    ctx.set_overlap(2)
+    src = FrameSource(spec, dev)
+    out = torch.empty((L, spec.n_heads, n, spec.head_dim), dtype=torch.bfloat16, device=dev)
+    times, rows = [], []
+    for f in range(frames):
+        q, k, v = src.frame(f)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for l in range(L):
+            ctx.step(l, q[l], k[l], v[l], out[l])
+        ctx.join()
+        e1.record()
+        torch.cuda.synchronize()
+        times.append(e0.elapsed_time(e1))
+        if (f + 1) in checkpoints:
+            w = times[-window:]
+            T = ctx.cache_len(0)
+            rows.append({"frame": f + 1, "ms_per_frame": round(sum(w) / len(w), 4), "cache_tokens": T,
+                         "cache_MB": round(cache_bytes(spec, T) / 1e6, 1), "attend_workgroups": ctx.last_attend_workgroups()})
+    ctx.destroy()
+    return rows
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--configs", default="", help="comma-separated workload ids of inputs.CONFIGS")
+    ap.add_argument("--frames", type=int, default=0, help="frames per workload for --configs (0 = saturation + 12)")
+    ap.add_argument("--long", type=int, default=0, help="frames of the long-stream comparison (0 = skip)")
+    args = ap.parse_args()
+
+    import torch
+    from paper_2602_21780_amd import xsv
+    from paper_2602_21780_amd.inputs import CONFIGS, FrameSource
+    if not torch.cuda.is_available():
+        print("stream_report: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+
+    for cid in [int(c) for c in args.configs.split(",") if c]:
+        spec = CONFIGS[cid]
+        n = spec.tokens_per_frame
+        sat = (spec.budget // n + 2) if spec.budget else 2
+        frames = args.frames or min(spec.frames, sat + 12)
+        rows = run_stream(spec, frames, {frames}, torch, xsv, FrameSource, window=max(1, min(10, frames - sat)))
+        r = rows[-1]
+        print(json.dumps({"workload": spec.name, "layers": spec.n_layers, "tokens_per_frame": n, "budget": spec.budget,
+                          "kv_bits": spec.kv_bits, "group_size": spec.group_size, "frames_run": frames,
+                          "frames_per_s": round(1e3 / r["ms_per_frame"], 2), **r}), flush=True)
+
+    if args.long:
+        base = CONFIGS[3]
+        marks = {m for m in (10, 25, 50, 100, 200, 500, 1000) if m <= args.long} | {args.long}
+        for label, spec in (("4-bit cache, budget 4096", base),
+                            ("bf16 cache, unbounded", base.with_(name="cfg3-unbounded-bf16", budget=0, kv_bits=16))):
+            for r in run_stream(spec, args.long, marks, torch, xsv, FrameSource):
+                print(json.dumps({"stream": label, **r, "frames_per_s": round(1e3 / r["ms_per_frame"], 2)}), flush=True)
+
+
+if __name__ == "__main__":
+    main()
