@@ -50,6 +50,33 @@ def test_quantize_degenerate_groups():
             assert np.array_equal(scale.cpu().numpy(), rs) and np.array_equal(zero.cpu().numpy(), rz)
 
 
+@pytest.mark.parametrize("bits", [2, 4])
+def test_quantize_quotients_on_and_next_to_rounding_boundaries(bits):
+    """Groups whose scale is exactly 1, 1/2 or 3 (quotients that are exact half-integers: ties to even, and
+    thirds next to them), groups far from zero (large zero points, large quotients) and tiny magnitudes: every
+    code must be the one IEEE division and round-half-to-even give."""
+    top = (1 << bits) - 1
+    g = torch.Generator().manual_seed(5)
+    x = torch.zeros((2, 256, 64))
+    k = torch.randint(0, 2 * top + 1, (2, 256, 64), generator=g).float() * 0.5       # multiples of 1/2 in [0, top]
+    x[:] = k
+    x[:, :, 0] = 0.0
+    x[:, :, 1] = float(top)                                                          # every token group spans [0, top]: s = 1
+    x[0, :, 8:16] = k[0, :, 8:16] * 0.5                                              # quarters
+    x[0, :, 16:24] = k[0, :, 16:24] * 3.0 + 300.0                                    # s = 3 on [300, 300 + 3 top]: zero point -100
+    x[1, :, 24:32] = k[1, :, 24:32] * 2.0 ** -100                                    # tiny scale
+    x[1, :, 32:40] = -4096.0 + k[1, :, 32:40]                                        # quotients in the thousands
+    x[0, 0::64, :] = 0.0
+    x[0, 1::64, :] = float(top)                                                      # every channel group spans at least [0, top]
+    xb = x.to(torch.bfloat16).to(DEV)
+    for fn_gpu, fn_ref in ((xsv.quantize_k, ref.quantize_k), (xsv.quantize_v, ref.quantize_v)):
+        for G in (32, 64):
+            codes, scale, zero = fn_gpu(xb, bits, G)
+            rc, rs, rz = fn_ref(to_u16(xb), bits, G)
+            assert np.array_equal(scale.cpu().numpy(), rs) and np.array_equal(zero.cpu().numpy(), rz)
+            assert np.array_equal(codes.cpu().numpy(), rc)
+
+
 @pytest.mark.parametrize("H,n,n_s,P,g", [(2, 64, 5, 192, 16), (16, 1374, 5, 2722, 16), (3, 37, 5, 70, 4), (1, 21, 0, 1, 1)])
 def test_score_matches_oracle(H, n, n_s, P, g):
     print(f"score H={H} n={n} P={P}", flush=True)
