@@ -318,9 +318,18 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
   // tiles of a unit: cache blocks, then the frame's own tokens (each range padded to 64 on its own)
   const int n_ct = (Tc + kTile - 1) / kTile, n_ft = (n + kTile - 1) / kTile;
   const Partition part{(long long)a.b.n_layers * H * nqb * (n_ct + n_ft), n_ct + n_ft, (int)gridDim.x};
-  const long long piece_end = part.begin(blockIdx.x + 1);
+  // Logical workgroup.  Workgroups whose blockIdx agree modulo 8 run on the same XCD and share its L2;
+  // when every unit is cut into the same number of key ranges, the query blocks of one (layer, head,
+  // key range) — which read the same K/V tiles — are placed on one XCD.
+  int wg = blockIdx.x;
+  if (a.xcd_ranges > 0) {
+    const int xcd = wg & 7, slot = wg >> 3;
+    const int g = (slot / nqb) * 8 + xcd;  // (layer, head, key range) triple
+    wg = ((g / a.xcd_ranges) * nqb + slot % nqb) * a.xcd_ranges + g % a.xcd_ranges;
+  }
+  const long long piece_end = part.begin(wg + 1);
 
-  for (long long pos = part.begin(blockIdx.x); pos < piece_end;) {
+  for (long long pos = part.begin(wg); pos < piece_end;) {
   const int unit = part.unit_of(pos);
   const int t_begin = (int)(pos - (long long)unit * part.n_tiles);
   const int t_end = (int)min((long long)part.n_tiles, t_begin + (piece_end - pos));
@@ -568,10 +577,13 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
     } else {
       // Partial of a cut unit, as fp16 mantissas under one power-of-two scale per query row (the
       // row's largest magnitude maps into [0.5, 1): 11 bits below the row maximum, half the bytes of
-      // fp32).  Lane (j, hh) owns 32 channels of row j and writes them as one 64-byte run, in
-      // register order: o0[0..15], o1[0..15].
-      const int piece = (int)blockIdx.x - part.first_wg(unit);
+      // fp32).  Lane (j, hh) owns 32 channels of row j, in register order o0[0..15], o1[0..15], as
+      // four 16-byte pieces i; a block of 32 rows is stored [i][hh][j], so that every store
+      // instruction of the wave covers 1 KB of consecutive memory.
+      const int piece = wg - part.first_wg(unit);
+      const int nblk = (n + 31) / 32;
       const size_t row = (((size_t)piece * a.b.n_layers + lb) * H + h) * n + q_row;
+      const size_t blk = (((size_t)piece * a.b.n_layers + lb) * H + h) * nblk + (q_row >> 5);
       float amax = 0.f;
 #pragma unroll
       for (int r = 0; r < 16; ++r) amax = fmaxf(amax, fmaxf(fabsf(o0[cb][r]), fabsf(o1[cb][r])));
@@ -583,9 +595,9 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
         hw[r >> 1] = pack_f16(__builtin_amdgcn_ldexpf(o0[cb][r], -e), __builtin_amdgcn_ldexpf(o0[cb][r + 1], -e));
         hw[8 + (r >> 1)] = pack_f16(__builtin_amdgcn_ldexpf(o1[cb][r], -e), __builtin_amdgcn_ldexpf(o1[cb][r + 1], -e));
       }
-      uint4* op = reinterpret_cast<uint4*>(a.ws.attn_o + (row * 2 + hh) * 32);
+      uint4* op = reinterpret_cast<uint4*>(a.ws.attn_o) + blk * 256 + hh * 32 + j;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) op[i] = make_uint4(hw[4 * i], hw[4 * i + 1], hw[4 * i + 2], hw[4 * i + 3]);
+      for (int i = 0; i < 4; ++i) op[i * 64] = make_uint4(hw[4 * i], hw[4 * i + 1], hw[4 * i + 2], hw[4 * i + 3]);
       if (hh == 0)
         *reinterpret_cast<float4*>(a.ws.attn_ml + row * 4) = make_float4(m[cb] * c2, lsum, __builtin_amdgcn_ldexpf(1.0f, e), 0.f);
     }
@@ -615,11 +627,13 @@ __global__ __launch_bounds__(256) void combine_kernel(const AttendArgs a) {
   const int S = part.last_wg(unit) - w0 + 1;
   const int qb = unit % nqb, h = (unit / nqb) % H, lb = unit / (nqb * H);
   const int tid = threadIdx.x;
-  const int q_row = qb * a.rows_wg + 32 * blockIdx.y + (tid >> 3);
-  const int hh = (tid >> 2) & 1, qd = tid & 3;
+  const int jrow = tid & 31, hh = (tid >> 5) & 1, qd = tid >> 6;  // consecutive threads read consecutive 16-byte pieces
+  const int q_row = qb * a.rows_wg + 32 * blockIdx.y + jrow;
   if (q_row >= n) return;
-  const size_t rows = (size_t)a.b.n_layers * H * n;
+  const int nblk = (n + 31) / 32;
+  const size_t rows = (size_t)a.b.n_layers * H * n, blks = (size_t)a.b.n_layers * H * nblk;
   const size_t row = ((size_t)lb * H + h) * n + q_row;
+  const size_t blk = ((size_t)lb * H + h) * nblk + (q_row >> 5);
   float ms[kMaxPieces], ls[kMaxPieces], sc[kMaxPieces];
   float M = kNegBig;
 #pragma unroll 4
@@ -634,7 +648,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const AttendArgs a) {
 #pragma unroll 4
   for (int s = 0; s < S; ++s) {
     const float wgt = __builtin_amdgcn_exp2f(ms[s] - M);
-    const uint4 o = *reinterpret_cast<const uint4*>(a.ws.attn_o + ((s * rows + row) * 2 + hh) * 32 + 8 * qd);
+    const uint4 o = reinterpret_cast<const uint4*>(a.ws.attn_o)[(s * blks + blk) * 256 + qd * 64 + hh * 32 + jrow];
     L += wgt * ls[s];
     const float ws = wgt * sc[s];
     const uint32_t ow[4] = {o.x, o.y, o.z, o.w};
@@ -688,7 +702,7 @@ AttendPlan plan_attend(int variant, int n_layers, int H, int n, int Tc, int want
   // a piece never shorter than 4 tiles (unless a whole unit is), never more workgroups than items
   long long w = std::max<long long>(1, std::min<long long>(want_wgs, std::max<long long>(n_units, total / 4)));
   // the partial workspace holds `fit` pieces of every row, the merge at most kMaxPieces
-  const int fit = (int)std::min<size_t>(kMaxPieces, part_rows / ((size_t)n_layers * H * n));
+  const int fit = (int)std::min<size_t>(kMaxPieces, part_rows / ((size_t)n_layers * H * ((n + 31) / 32 * 32)));
   AttendPlan p{};
   for (;; --w) {
     const Partition part{total, n_tiles, (int)w};

@@ -198,6 +198,11 @@ int do_attend(xsv_ctx* ctx, int layer0, int n_layers, const xsv_tensor* q, const
   a.n_wgs = plan.n_wgs;
   a.rows_wg = plan.rows_wg;
   a.cut = plan.max_pieces > 1;
+  {
+    const int n_units = ((a.n + plan.rows_wg - 1) / plan.rows_wg) * ctx->cfg.n_heads * n_layers;
+    const int ranges = plan.n_wgs % n_units == 0 ? plan.n_wgs / n_units : 0;
+    a.xcd_ranges = (ranges > 0 && (ctx->cfg.n_heads * n_layers * ranges) % 8 == 0) ? ranges : 0;
+  }
   ctx->last_attend_wgs = plan.n_wgs;
   a.qscale = ctx->cfg.softmax_scale * 1.4426950408889634f;
   if (launch_attend(a, ctx->stream) != hipSuccess) return hip_fail(ctx);
@@ -389,7 +394,8 @@ int xsv_create(const xsv_config* cfg, void* hip_stream, xsv_ctx** out) {
   A(&w.keep, (size_t)c.n_layers * w.scores_stride, true);
   A(&w.qpart, (size_t)c.n_layers * w.qpart_rows * kD, true);
   // partial attention outputs: up to 16 key ranges for one layer, or 2 per layer when batched
-  const size_t part_rows = (size_t)std::max(16, 2 * std::min(c.n_layers, kMaxBatch)) * c.n_heads * n;
+  // (partials are stored in blocks of 32 query rows per head)
+  const size_t part_rows = (size_t)std::max(16, 2 * std::min(c.n_layers, kMaxBatch)) * c.n_heads * round_up((int)n, 32);
   ctx->part_rows = part_rows;
   A(&w.attn_o, part_rows * kD, false);
   A(&w.attn_ml, part_rows * 4, false);

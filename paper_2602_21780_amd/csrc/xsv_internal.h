@@ -86,7 +86,8 @@ struct Workspace {
   float* scores;      // [L][Tcap + n]      importance of the middle tokens
   int32_t* keep;      // [L][Tcap + n]      keep list
   float* qpart;       // [L][qpart_rows][64] partial weighted query sums
-  uint16_t* attn_o;   // [pieces][batch layers][H][n][2][32] fp16 mantissas of the unnormalized partial outputs
+  uint16_t* attn_o;   // [pieces][batch layers][H][ceil(n/32)] blocks of 32 rows x 64 fp16 mantissas of the unnormalized
+                      // partial outputs, each block stored [16-byte piece 0..3][lane half][row] (4 KB)
   float* attn_ml;     // [pieces][batch layers][H][n][4]  softmax reference (log2 domain), row sum, row scale, -
   int scores_stride;  // Tcap + n
   int qpart_rows;
@@ -103,6 +104,7 @@ struct AttendArgs {
   int n_wgs;     // workgroups the (unit, tile) line is cut into (from plan_attend)
   int rows_wg;   // query rows per workgroup of this variant
   int cut;       // some unit is shared by several workgroups: partials are written and merged
+  int xcd_ranges;  // > 0: every unit is cut into this many key ranges and the grid is permuted for L2 sharing
   float qscale;  // softmax scale * log2(e)
 };
 constexpr int kMaxPieces = 16;  // workgroups that may share one unit
