@@ -5,11 +5,15 @@ per-frame cost stay constant; Sec. 4.4 reports the same comparison on video stre
 
     python -m paper_2602_21780_amd.stream_report --configs 0,1,2,4
     python -m paper_2602_21780_amd.stream_report --long 200
+    python -m paper_2602_21780_amd.stream_report --granularity
 
 `--configs`: frames/s of each listed workload at its saturated cache, layer by layer through xsv_step
 (overlap mode 2, one xsv_join per frame), events on the launch stream around each frame's 24 (or 1) steps.
 `--long N`: the 24-layer drifting stream for N frames, once with the 4-bit budgeted cache and once with an
 unbounded bf16 cache (kv_bits 16, budget 0); prints ms/frame and cache bytes at checkpoints.
+`--granularity`: mean squared error of the two grouping directions of the quantizer (per token: groups of G
+channels; per channel: groups of G tokens) on the synthetic keys (with their outlier channels) and values, at
+4 and 2 bits, G = 64 — the analogue of the paper's Table 1 (Sec. 3.3), through xsv_quantize_k / xsv_quantize_v.
 Inputs are synthetic (seeded), generated on the device outside the timed regions.  One JSON line per row.
 """
 from __future__ import annotations
@@ -56,11 +60,38 @@ def run_stream(spec, frames, checkpoints, torch, xsv, FrameSource, window=5):
     return rows
 
 
+def granularity_table(torch, xsv, FrameSource, CONFIGS, G=64):
+    """MSE of (codes - zero) * scale against the bf16 input for both grouping directions."""
+    spec = CONFIGS[2]
+    src = FrameSource(spec, "cuda:0", layers=[0])
+    frames = [src.frame(f) for f in range(3)]
+    rows = []
+    for name, idx in (("keys", 1), ("values", 2)):
+        x = torch.cat([fr[idx][0] for fr in frames], dim=1).contiguous()       # [H][3n][64] bf16
+        xf = x.float()
+        T = x.shape[1]
+        for bits in (4, 2):
+            mse = {}
+            for label, fn in (("per_token", xsv.quantize_v), ("per_channel", xsv.quantize_k)):
+                codes, scale, zero = fn(x, bits, G)
+                if label == "per_channel":                                        # [H][ceil(T/G)][64] -> tokens
+                    scale, zero = (t.repeat_interleave(G, dim=1)[:, :T] for t in (scale, zero))
+                else:                                                             # [H][T][64/G] -> channels
+                    scale, zero = (t.repeat_interleave(G, dim=2) for t in (scale, zero))
+                xhat = (codes.float() - zero) * scale
+                mse[label] = float(((xhat - xf) ** 2).mean())
+            rows.append({"tensor": name, "bits": bits, "group_size": G, "tokens": T, "mse_per_token": mse["per_token"],
+                         "mse_per_channel": mse["per_channel"],
+                         "ratio_token_over_channel": round(mse["per_token"] / mse["per_channel"], 3)})
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--configs", default="", help="comma-separated workload ids of inputs.CONFIGS")
     ap.add_argument("--frames", type=int, default=0, help="frames per workload for --configs (0 = saturation + 12)")
     ap.add_argument("--long", type=int, default=0, help="frames of the long-stream comparison (0 = skip)")
+    ap.add_argument("--granularity", action="store_true", help="per-token vs per-channel quantization error table")
     args = ap.parse_args()
 
     import torch
@@ -80,6 +111,10 @@ def main():
         print(json.dumps({"workload": spec.name, "layers": spec.n_layers, "tokens_per_frame": n, "budget": spec.budget,
                           "kv_bits": spec.kv_bits, "group_size": spec.group_size, "frames_run": frames,
                           "frames_per_s": round(1e3 / r["ms_per_frame"], 2), **r}), flush=True)
+
+    if args.granularity:
+        for r in granularity_table(torch, xsv, FrameSource, CONFIGS):
+            print(json.dumps(r), flush=True)
 
     if args.long:
         base = CONFIGS[3]
