@@ -10,7 +10,8 @@ CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libxsv.so")
 BUILD_DIR = os.path.join(_HERE, "_build")
 
-# packed-fp32 instructions are switched off for every kernel (target feature), see the design doc
+# packed-fp32 instructions are switched off for every kernel (target feature): some of their forms have
+# given wrong results on this hardware, and hipcc would otherwise form them from ordinary float code
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
           "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 # bit-exact kernels: one rounding per operation, like the definition
