@@ -609,22 +609,29 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
 // Merge of the pieces of every unit that was cut:  out = sum_p 2^(m_p - M) O_p / sum_p 2^(m_p - M) l_p.
 // (A separate launch on purpose: a device-wide release/acquire inside the attention kernel costs an
 // L2 write-back per workgroup on this multi-die part, far more than a second small kernel.)
-// Grid: x = boundary between workgroups w-1 | w of the attention grid (w = blockIdx.x + 1), y = chunk
-// of 32 query rows of the unit that boundary falls into.  A unit with several boundaries is handled
-// at its first one; a boundary that coincides with a unit's edge has nothing to merge.
+// Grid: y = chunk of 32 query rows of a unit; x = the unit when all units are cut alike, else a boundary
+// between workgroups w-1 | w of the attention grid (w = blockIdx.x + 1), standing for the unit it falls
+// into: a unit with several boundaries is handled at its first one, and a boundary that coincides with
+// a unit's edge has nothing to merge.
 // Thread = (row, lane half hh, quarter of the lane's 32 values): 8 fp16 values of every piece.
 __global__ __launch_bounds__(256) void combine_kernel(const AttendArgs a) {
   const int H = a.pool.H, n = a.n;
   const int nqb = (n + a.rows_wg - 1) / a.rows_wg;
   const int n_tiles = (a.Tc + kTile - 1) / kTile + (n + kTile - 1) / kTile;
   const Partition part{(long long)a.b.n_layers * H * nqb * n_tiles, n_tiles, a.n_wgs};
-  const int w = blockIdx.x + 1;
-  const long long pos = part.begin(w);
-  const int unit = part.unit_of(pos);
-  if (pos == (long long)unit * n_tiles) return;
-  const int w0 = part.first_wg(unit);
-  if (w0 + 1 != w) return;
-  const int S = part.last_wg(unit) - w0 + 1;
+  int unit, S;
+  if (a.equal_ranges > 0) {  // every unit is cut into the same number of ranges: x = unit
+    unit = blockIdx.x;
+    S = a.equal_ranges;
+  } else {
+    const int w = blockIdx.x + 1;
+    const long long pos = part.begin(w);
+    unit = part.unit_of(pos);
+    if (pos == (long long)unit * n_tiles) return;
+    const int w0 = part.first_wg(unit);
+    if (w0 + 1 != w) return;
+    S = part.last_wg(unit) - w0 + 1;
+  }
   const int qb = unit % nqb, h = (unit / nqb) % H, lb = unit / (nqb * H);
   const int tid = threadIdx.x;
   const int jrow = tid & 31, hh = (tid >> 5) & 1, qd = tid >> 6;  // consecutive threads read consecutive 16-byte pieces
@@ -673,7 +680,9 @@ static hipError_t launch_attend_t(const AttendArgs& a, hipStream_t stream) {
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (a.cut) {
-    hipLaunchKernelGGL(combine_kernel, dim3(a.n_wgs - 1, (a.rows_wg + 31) / 32), dim3(256), 0, stream, a);
+    const int n_units = a.b.n_layers * a.pool.H * ((a.n + a.rows_wg - 1) / a.rows_wg);
+    hipLaunchKernelGGL(combine_kernel, dim3(a.equal_ranges > 0 ? n_units : a.n_wgs - 1, (a.rows_wg + 31) / 32), dim3(256), 0,
+                       stream, a);
     e = hipGetLastError();
   }
   return e;

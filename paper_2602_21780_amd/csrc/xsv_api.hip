@@ -201,6 +201,7 @@ int do_attend(xsv_ctx* ctx, int layer0, int n_layers, const xsv_tensor* q, const
   {
     const int n_units = ((a.n + plan.rows_wg - 1) / plan.rows_wg) * ctx->cfg.n_heads * n_layers;
     const int ranges = plan.n_wgs % n_units == 0 ? plan.n_wgs / n_units : 0;
+    a.equal_ranges = ranges > 1 ? ranges : 0;
     a.xcd_ranges = (ranges > 0 && (ctx->cfg.n_heads * n_layers * ranges) % 8 == 0) ? ranges : 0;
   }
   ctx->last_attend_wgs = plan.n_wgs;

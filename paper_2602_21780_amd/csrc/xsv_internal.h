@@ -104,6 +104,7 @@ struct AttendArgs {
   int n_wgs;     // workgroups the (unit, tile) line is cut into (from plan_attend)
   int rows_wg;   // query rows per workgroup of this variant
   int cut;       // some unit is shared by several workgroups: partials are written and merged
+  int equal_ranges;  // > 0: every unit is cut into exactly this many key ranges
   int xcd_ranges;  // > 0: every unit is cut into this many key ranges and the grid is permuted for L2 sharing
   float qscale;  // softmax scale * log2(e)
 };
