@@ -218,3 +218,33 @@ def test_2bit_config_shape_sampled_rows():
     spec = CONFIGS[4].with_(n_layers=1)
     rows = np.array([0, 5, 1000, 1040], np.int32)
     run_stream(spec, 9, rows=rows)
+
+
+def test_24_layer_config_as_benchmarked_three_layers_checked():
+    """cfg 2 with all 24 layers in the launch configuration bench.py times (overlap mode 2, one join per
+    frame, default attention grid); the oracle follows layers 0, 11 and 23 (cache bytes in full, attention
+    on sampled rows), the other layers only run."""
+    spec = CONFIGS[2]
+    checked = [0, 11, 23]
+    ctx, st = parity.make_pair(spec, layers=checked)
+    ctx.set_overlap(2)
+    src = FrameSource(spec, DEV)
+    rows = np.array([0, 4, 5, 511, 512, 1023, 1024, 1373], np.int32)
+    frames = [src.frame(f) for f in range(6)]          # kept alive, as overlap mode 2 requires
+    out = torch.empty((spec.n_layers, spec.n_heads, spec.tokens_per_frame, spec.head_dim), dtype=torch.bfloat16, device=DEV)
+    worst, ties = (0.0, 0.0), 0
+    for f, (q, k, v) in enumerate(frames):
+        for l in range(spec.n_layers):
+            if l in checked:
+                print(f"  {spec.name} frame {f} layer {l} T={ctx.cache_len(l)}", flush=True)
+                (ma, rr), t = parity.step_and_compare(ctx, st, spec, l, checked.index(l), q[l], k[l], v[l], rows=rows)
+                worst, ties = (max(worst[0], ma), max(worst[1], rr)), ties + t
+            else:
+                ctx.step(l, q[l], k[l], v[l], out[l])
+        ctx.join()
+    torch.cuda.synchronize()
+    assert ctx.last_attend_workgroups() > 0
+    for l in range(spec.n_layers):
+        assert ctx.cache_len(l) == spec.budget
+    print(f"  worst max_abs={worst[0]:.3e} rel_rms={worst[1]:.3e} ties={ties} grid={ctx.last_attend_workgroups()}", flush=True)
+    ctx.destroy()
