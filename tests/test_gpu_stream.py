@@ -248,3 +248,16 @@ def test_24_layer_config_as_benchmarked_three_layers_checked():
         assert ctx.cache_len(l) == spec.budget
     print(f"  worst max_abs={worst[0]:.3e} rel_rms={worst[1]:.3e} ties={ties} grid={ctx.last_attend_workgroups()}", flush=True)
     ctx.destroy()
+
+
+@pytest.mark.parametrize("n,n_s,H,budget,bits,G", [
+    (1, 1, 1, 3, 4, 32),       # one special token per frame and nothing else: no patch rows to pool
+    (7, 5, 1, 16, 2, 32),      # two patch rows: a single short pooled group
+    (6, 0, 2, 12, 4, 64),      # no special tokens; budget exactly first + current: k = 0 from the third frame on
+    (33, 5, 3, 100, 4, 32),    # one row past a 32-row block; budget leaves k = 34 of a growing middle
+    (65, 5, 2, 131, 16, 64),   # bf16 cache, one token past a key tile, k = 1
+])
+def test_degenerate_and_smallest_shapes(n, n_s, H, budget, bits, G):
+    spec = CONFIGS[0].with_(name=f"small-n{n}", n_heads=H, tokens_per_frame=n, n_special=n_s, budget=budget,
+                            kv_bits=bits, group_size=G, n_layers=1, seed=21 + n)
+    run_stream(spec, 7)
