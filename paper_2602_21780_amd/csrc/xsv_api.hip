@@ -496,12 +496,20 @@ static int step_layers(xsv_ctx* ctx, int layer0, int n_layers, const xsv_tensor*
     if (hipEventRecord(ctx->ev_fork, ctx->stream) != hipSuccess || hipStreamWaitEvent(ctx->side, ctx->ev_fork, 0) != hipSuccess)
       return hip_fail(ctx);
   }
-  rc = do_attend(ctx, layer0, n_layers, q, k, v, out, splits, fork ? ctx->side_cus : 0);
-  if (rc == XSV_OK) {
-    ctx->work = fork ? ctx->side : ctx->stream;
+  if (fork) {
+    // the chain is enqueued first: its launches then do not queue up behind the host time of the
+    // attention launches, and it starts as soon as the fork event fires
+    ctx->work = ctx->side;
     rc = do_score_prune(ctx, layer0, n_layers, q);
+    ctx->work = ctx->stream;
+    if (rc == XSV_OK) rc = do_attend(ctx, layer0, n_layers, q, k, v, out, splits, ctx->side_cus);
+    ctx->work = ctx->side;
     if (rc == XSV_OK) rc = do_quantize(ctx, layer0, n_layers, k, v);
     ctx->work = ctx->stream;
+  } else {
+    rc = do_attend(ctx, layer0, n_layers, q, k, v, out, splits, 0);
+    if (rc == XSV_OK) rc = do_score_prune(ctx, layer0, n_layers, q);
+    if (rc == XSV_OK) rc = do_quantize(ctx, layer0, n_layers, k, v);
   }
   if (fork && ctx->overlap == 2) {
     if (hipEventRecord(ctx->ev_chain[layer0], ctx->side) != hipSuccess) return hip_fail(ctx);
