@@ -370,6 +370,7 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
 
   f32x16 o0[QB], o1[QB];
   float m[QB], l[QB];  // running max of the raw logits, this lane's share of the row sum
+  const float lazy_gap = kLazyLog2 / c2;
 #pragma unroll
   for (int cb = 0; cb < QB; ++cb) {
 #pragma unroll
@@ -400,7 +401,7 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
     // the reference maximum only moves when some row's maximum grows by more than 2^kLazyLog2;
     // until then probabilities may exceed 1 (by at most that factor), which fp32 sums and
     // bf16 products absorb, and the accumulators need no rescaling
-    if (__any((mx - mref) * c2 > kLazyLog2)) {
+    if (__any(mx > mref + lazy_gap)) {  // lazy_gap = kLazyLog2 / c2: one add and one compare per half-step
       const float m_new = fmaxf(mref, mx);
       const float alpha = __builtin_amdgcn_exp2f((mref - m_new) * c2);
       lsum *= alpha;

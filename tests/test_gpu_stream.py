@@ -261,3 +261,43 @@ def test_degenerate_and_smallest_shapes(n, n_s, H, budget, bits, G):
     spec = CONFIGS[0].with_(name=f"small-n{n}", n_heads=H, tokens_per_frame=n, n_special=n_s, budget=budget,
                             kv_bits=bits, group_size=G, n_layers=1, seed=21 + n)
     run_stream(spec, 7)
+
+
+def test_step_can_be_captured_in_a_graph_and_replayed():
+    """xsv_step enqueues only kernels and event record/wait pairs, so a stream capture takes it whole (the
+    side stream joins the capture through the fork event and leaves it through the join event).  A replay
+    repeats the captured step from the same source buffer: every replay must reproduce the eager output,
+    with eager work of this process between the replays."""
+    spec = CONFIGS[0].with_(name="graph", n_layers=1, n_heads=4, tokens_per_frame=150, budget=400, group_size=64, seed=13)
+    src = FrameSource(spec, DEV)
+    frames = [src.frame(f) for f in range(5)]
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        ctx_e = xsv.Context.from_spec(spec)        # eager twin
+        ctx_g = xsv.Context.from_spec(spec)        # the last step of this one is captured
+        for ctx in (ctx_e, ctx_g):
+            ctx.set_attend_splits(2, 2)
+        for f in range(4):
+            q, k, v = frames[f]
+            ctx_e.step(0, q[0], k[0], v[0])
+            ctx_g.step(0, q[0], k[0], v[0])
+        q, k, v = frames[4]
+        want = ctx_e.step(0, q[0], k[0], v[0]).clone()
+        want_cache = ctx_e.cache_export(0)
+        out = torch.zeros_like(want)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=s):
+            ctx_g.step(0, q[0], k[0], v[0], out)
+        torch.cuda.synchronize()
+        for rep in range(3):
+            out.zero_()
+            scratch = (torch.randn(1 << 16, device=DEV) * 2).sum()     # unrelated eager work and a sync between replays
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out, want), f"replay {rep} differs from the eager step"
+            assert torch.isfinite(scratch)
+        parity.compare_cache(ctx_g.cache_export(0), want_cache, True)   # the host state advanced once, at capture
+    ctx_e.destroy()
+    ctx_g.destroy()
