@@ -81,7 +81,7 @@ def main():
 
     # ---- inputs, resident in HBM before anything is timed -------------------------------------------
     src = FrameSource(spec, dev)
-    frames = [src.frame(f) for f in range(max(W + K + S, 5 + args.cpu_steps))]
+    frames = [src.frame(f) for f in range(max(W + K + 2 * S, 5 + args.cpu_steps))]
     out = torch.empty((L, spec.n_heads, n, spec.head_dim), dtype=torch.bfloat16, device=dev)
     ctx = xsv.Context.from_spec(spec)
     ctx.set_attend_splits(args.splits, args.splits)
@@ -132,45 +132,61 @@ def main():
     # ---- per-stage durations with events on the launch stream (steady state) --------------------------
     # Each stage is launched for all 24 layers back to back between two events (the layers are
     # independent of each other), so one event pair brackets 24 launches and its own cost is amortized.
+    # The attention launches are additionally bracketed inside the library (before the attention
+    # kernel, between it and the merge kernel, after), which separates the two kernels.
     ctx.join()
     n_units = spec.n_heads * ((n + 511) // 512)
     if args.splits == 0 and step_wgs % n_units == 0:
         ctx.set_attend_splits(step_wgs // n_units, 0)   # the grid the timed steps used (they leave units to the chain)
     ev = lambda: torch.cuda.Event(enable_timing=True)
     stage_ms = {"attend": 0.0, "score_prune": 0.0, "quantize": 0.0}
-    marks = []
-    for f in range(W + K, W + K + S):
-        q, k, v = frames[f]
-        e = [ev() for _ in range(4)]
-        e[0].record()
-        for l in range(L):
-            ctx.dequant_attend(l, q[l], k[l], v[l], out[l])
-        e[1].record()
-        for l in range(L):
-            ctx.score_prune(l, q[l])
-        e[2].record()
-        for l in range(L):
-            ctx.quantize(l, k[l], v[l])
-        e[3].record()
-        marks.append(e)
-    torch.cuda.synchronize()
+
+    def stage_pass(f0):
+        marks = []
+        for f in range(f0, f0 + S):
+            q, k, v = frames[f]
+            e = [ev() for _ in range(4)]
+            e[0].record()
+            for l in range(L):
+                ctx.dequant_attend(l, q[l], k[l], v[l], out[l])
+            e[1].record()
+            for l in range(L):
+                ctx.score_prune(l, q[l])
+            e[2].record()
+            for l in range(L):
+                ctx.quantize(l, k[l], v[l])
+            e[3].record()
+            marks.append(e)
+        torch.cuda.synchronize()
+        return marks
+
+    marks = stage_pass(W + K)                      # amortized: one event pair per 24 launches of a stage
     for e in marks:
         stage_ms["attend"] += e[0].elapsed_time(e[1]) / (L * len(marks))
         stage_ms["score_prune"] += e[1].elapsed_time(e[2]) / (L * len(marks))
         stage_ms["quantize"] += e[2].elapsed_time(e[3]) / (L * len(marks))
+    ctx.set_attend_timing(True)                    # the same again with the library's events around each kernel
+    stage_pass(W + K + S)
+    n_timed_launches, attend_span_ms, merge_span_ms, event_ms = ctx.attend_times()
+    ctx.set_attend_timing(False)
+    # a span between two events holds the kernel plus what the closing event itself takes
+    attend_kernel_ms, merge_kernel_ms = attend_span_ms - event_ms, merge_span_ms - event_ms
     Tn = ctx.cache_len(0)
     P = Tc + n - 2 * n
     work = algorithmic_work(spec, Tc, Tn, P)
-    attend_tflops = work["attend_flop"] / (stage_ms["attend"] * 1e-3) / 1e12
+    attend_tflops = work["attend_flop"] / (attend_kernel_ms * 1e-3) / 1e12
     roofline = {
-        "kernel": "attend_kernel<4,64> (+ combine_kernel when key ranges are split)",
+        "kernel": "attend_kernel<4,64,8,2>",
         "bound": "mfma", "achieved": round(attend_tflops, 2), "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
         "frac": round(attend_tflops / PEAK_BF16_MFMA_TFLOPS, 4),
         "traffic": TRAFFIC_ATTEND_CFG2["bytes"] if ctx.last_attend_workgroups() == TRAFFIC_ATTEND_CFG2["workgroups"] else None,
         "traffic_unit": "bytes per attend_kernel launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, profiles/attend_cfg2_hbm_traffic.md)",
         "algorithmic_bytes": work["attend_bytes"],
-        "flop_per_launch": work["attend_flop"], "avg_launch_ms": round(stage_ms["attend"], 4),
+        "flop_per_launch": work["attend_flop"], "avg_launch_ms": round(attend_kernel_ms, 4), "launches_timed": n_timed_launches,
         "workgroups": ctx.last_attend_workgroups(),
+        "merge_kernel_ms": round(merge_kernel_ms, 4), "event_pair_ms": round(event_ms, 4),
+        "attend_plus_merge_ms": round(stage_ms["attend"], 4),
+        "attend_plus_merge_TFLOPs": round(work["attend_flop"] / (stage_ms["attend"] * 1e-3) / 1e12, 2),
     }
     hbm = {
         "score_prune_GBs": round(work["score_bytes"] / (stage_ms["score_prune"] * 1e-3) / 1e9, 1),

@@ -137,6 +137,16 @@ int xsv_join(xsv_ctx* ctx);
  * overlapped score/select/re-quantize chain (default 64; 0 .. half the chip).  Without spare units
  * the chain only starts when attention drains.  Ignored when overlap is off or splits are fixed. */
 int xsv_set_side_cus(xsv_ctx* ctx, int compute_units);
+/* Measurement aid.  While enabled, every attention launch of this context (xsv_dequant_attend, xsv_step,
+ * xsv_step_all_layers) is bracketed by events on the context's stream: before the attention kernel,
+ * between it and the kernel that merges key-range partials, after, and once more right behind.
+ * xsv_attend_times waits for the stream, returns the number of launches recorded since the last call (or
+ * since enabling), the average span of each of the two kernels in milliseconds and (event_ms, may be NULL)
+ * the average span of the last two events, which have nothing between them: what an event pair itself adds
+ * to a span.  It then starts a new series.  Enabling or disabling discards the series.  The events cost a
+ * few microseconds per launch; leave this off in production. */
+int xsv_set_attend_timing(xsv_ctx* ctx, int enabled);
+int xsv_attend_times(xsv_ctx* ctx, int32_t* launches, float* attend_ms, float* merge_ms, float* event_ms);
 /* Grid (workgroups) of the most recent attention launch of this context, 0 before the first. */
 int xsv_last_attend_workgroups(xsv_ctx* ctx, int32_t* workgroups);
 /* Tuning: workgroup shape of the attention kernel (waves x query rows per wave).  3 (default) = 8 x 64,

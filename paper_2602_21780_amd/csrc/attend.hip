@@ -676,10 +676,11 @@ __global__ __launch_bounds__(256) void combine_kernel(const AttendArgs a) {
 }
 
 template <int BITS, int G, int NW, int QB>
-static hipError_t launch_attend_t(const AttendArgs& a, hipStream_t stream) {
+static hipError_t launch_attend_t(const AttendArgs& a, hipStream_t stream, hipEvent_t between) {
   hipLaunchKernelGGL((attend_kernel<BITS, G, NW, QB>), dim3(a.n_wgs), dim3(NW * 64), 0, stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  if (between && (e = hipEventRecord(between, stream)) != hipSuccess) return e;
   if (a.cut) {
     const int n_units = a.b.n_layers * a.pool.H * ((a.n + a.rows_wg - 1) / a.rows_wg);
     hipLaunchKernelGGL(combine_kernel, dim3(a.equal_ranges > 0 ? n_units : a.n_wgs - 1, (a.rows_wg + 31) / 32), dim3(256), 0,
@@ -690,12 +691,12 @@ static hipError_t launch_attend_t(const AttendArgs& a, hipStream_t stream) {
 }
 
 template <int BITS, int G>
-static hipError_t launch_attend_v(const AttendArgs& a, hipStream_t stream) {
+static hipError_t launch_attend_v(const AttendArgs& a, hipStream_t stream, hipEvent_t between) {
   switch (a.variant) {
-    case 1: return launch_attend_t<BITS, G, 4, 1>(a, stream);
-    case 2: return launch_attend_t<BITS, G, 8, 1>(a, stream);
-    case 3: return launch_attend_t<BITS, G, 8, 2>(a, stream);
-    default: return launch_attend_t<BITS, G, 4, 2>(a, stream);
+    case 1: return launch_attend_t<BITS, G, 4, 1>(a, stream, between);
+    case 2: return launch_attend_t<BITS, G, 8, 1>(a, stream, between);
+    case 3: return launch_attend_t<BITS, G, 8, 2>(a, stream, between);
+    default: return launch_attend_t<BITS, G, 4, 2>(a, stream, between);
   }
 }
 
@@ -728,13 +729,13 @@ AttendPlan plan_attend(int variant, int n_layers, int H, int n, int Tc, int want
   }
 }
 
-hipError_t launch_attend(const AttendArgs& a, hipStream_t stream) {
+hipError_t launch_attend(const AttendArgs& a, hipStream_t stream, hipEvent_t between) {
   const int bits = a.pool.bits, G = a.pool.G;
-  if (bits == 16) return launch_attend_v<16, 64>(a, stream);
-  if (bits == 4 && G == 64) return launch_attend_v<4, 64>(a, stream);
-  if (bits == 4 && G == 32) return launch_attend_v<4, 32>(a, stream);
-  if (bits == 2 && G == 64) return launch_attend_v<2, 64>(a, stream);
-  if (bits == 2 && G == 32) return launch_attend_v<2, 32>(a, stream);
+  if (bits == 16) return launch_attend_v<16, 64>(a, stream, between);
+  if (bits == 4 && G == 64) return launch_attend_v<4, 64>(a, stream, between);
+  if (bits == 4 && G == 32) return launch_attend_v<4, 32>(a, stream, between);
+  if (bits == 2 && G == 64) return launch_attend_v<2, 64>(a, stream, between);
+  if (bits == 2 && G == 32) return launch_attend_v<2, 32>(a, stream, between);
   return hipErrorInvalidValue;
 }
 

@@ -51,6 +51,11 @@ struct xsv_ctx {
   int splits_single = 0, splits_batched = 0;
   int attend_variant = 3;  // 8 waves x 64 query rows per workgroup
   int last_attend_wgs = 0;  // grid of the most recent attention launch
+  // optional timing of the attention launches: events before, between the two kernels, after, and one more
+  // right behind (the span of the last two, with nothing between them, is what an event pair itself costs)
+  bool timing = false;
+  std::vector<hipEvent_t> timing_events;
+  size_t timing_used = 0;
   int side_cus = 64;  // compute units xsv_step leaves to the prune chain while attention runs
   size_t part_rows = 0;  // rows the partial-output workspace holds
   int n_cu = 256;
@@ -92,6 +97,8 @@ void free_all(xsv_ctx* ctx) {
   if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
   if (ctx->ev_join) (void)hipEventDestroy(ctx->ev_join);
   for (hipEvent_t e : ctx->ev_chain) (void)hipEventDestroy(e);
+  for (hipEvent_t e : ctx->timing_events) (void)hipEventDestroy(e);
+  ctx->timing_events.clear();
   ctx->ev_chain.clear();
   ctx->side = nullptr;
   ctx->ev_fork = ctx->ev_join = nullptr;
@@ -206,7 +213,20 @@ int do_attend(xsv_ctx* ctx, int layer0, int n_layers, const xsv_tensor* q, const
   }
   ctx->last_attend_wgs = plan.n_wgs;
   a.qscale = ctx->cfg.softmax_scale * 1.4426950408889634f;
-  if (launch_attend(a, ctx->stream) != hipSuccess) return hip_fail(ctx);
+  hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+  if (ctx->timing) {
+    while (ctx->timing_events.size() < ctx->timing_used + 4) {
+      hipEvent_t e = nullptr;
+      if (hipEventCreate(&e) != hipSuccess) return hip_fail(ctx);
+      ctx->timing_events.push_back(e);
+    }
+    for (int i = 0; i < 4; ++i) ev[i] = ctx->timing_events[ctx->timing_used + i];
+    ctx->timing_used += 4;
+    if (hipEventRecord(ev[0], ctx->stream) != hipSuccess) return hip_fail(ctx);
+  }
+  if (launch_attend(a, ctx->stream, ev[1]) != hipSuccess) return hip_fail(ctx);
+  if (ev[2] && (hipEventRecord(ev[2], ctx->stream) != hipSuccess || hipEventRecord(ev[3], ctx->stream) != hipSuccess))
+    return hip_fail(ctx);
   for (int i = 0; i < n_layers; ++i) ctx->layers[layer0 + i].phase = kAttended;
   return XSV_OK;
 }
@@ -438,6 +458,37 @@ int xsv_set_attend_splits(xsv_ctx* ctx, int per_layer_calls, int batched_calls) 
   if (!ctx || per_layer_calls < 0 || per_layer_calls > 16 || batched_calls < 0 || batched_calls > 16) return XSV_ERR_ARG;
   ctx->splits_single = per_layer_calls;
   ctx->splits_batched = batched_calls;
+  return XSV_OK;
+}
+
+int xsv_set_attend_timing(xsv_ctx* ctx, int enabled) {
+  if (!ctx) return XSV_ERR_ARG;
+  ctx->timing = enabled != 0;
+  ctx->timing_used = 0;
+  return XSV_OK;
+}
+
+int xsv_attend_times(xsv_ctx* ctx, int32_t* launches, float* attend_ms, float* merge_ms, float* event_ms) {
+  if (!ctx || !launches || !attend_ms || !merge_ms) return XSV_ERR_ARG;
+  if (ctx->broken) return XSV_ERR_HIP;
+  if (hipStreamSynchronize(ctx->stream) != hipSuccess) return hip_fail(ctx);
+  double a = 0.0, m = 0.0, own = 0.0;
+  const size_t n = ctx->timing_used / 4;
+  for (size_t i = 0; i < n; ++i) {
+    float t0 = 0.f, t1 = 0.f, t2 = 0.f;
+    hipEvent_t* e = &ctx->timing_events[4 * i];
+    if (hipEventElapsedTime(&t0, e[0], e[1]) != hipSuccess || hipEventElapsedTime(&t1, e[1], e[2]) != hipSuccess ||
+        hipEventElapsedTime(&t2, e[2], e[3]) != hipSuccess)
+      return hip_fail(ctx);
+    a += t0;
+    m += t1;
+    own += t2;
+  }
+  *launches = (int32_t)n;
+  *attend_ms = n ? (float)(a / n) : 0.f;
+  *merge_ms = n ? (float)(m / n) : 0.f;
+  if (event_ms) *event_ms = n ? (float)(own / n) : 0.f;
+  ctx->timing_used = 0;
   return XSV_OK;
 }
 
