@@ -301,3 +301,22 @@ def test_step_can_be_captured_in_a_graph_and_replayed():
         parity.compare_cache(ctx_g.cache_export(0), want_cache, True)   # the host state advanced once, at capture
     ctx_e.destroy()
     ctx_g.destroy()
+
+
+def test_attention_timing_series():
+    spec = CONFIGS[0].with_(name="timing", n_layers=1, n_heads=4, tokens_per_frame=150, budget=400, group_size=64)
+    ctx = xsv.Context.from_spec(spec)
+    ctx.set_attend_splits(2, 2)
+    src = FrameSource(spec, DEV)
+    ctx.set_attend_timing(True)
+    for f in range(4):
+        q, k, v = src.frame(f)
+        ctx.step(0, q[0], k[0], v[0])
+    launches, attend_ms, merge_ms, event_ms = ctx.attend_times()
+    assert launches == 4 and attend_ms > 0.0 and merge_ms > 0.0 and event_ms > 0.0
+    assert ctx.attend_times()[0] == 0                      # a call starts a new series
+    ctx.set_attend_timing(False)
+    q, k, v = src.frame(4)
+    ctx.step(0, q[0], k[0], v[0])
+    assert ctx.attend_times()[0] == 0                      # nothing is recorded while it is off
+    ctx.destroy()
