@@ -197,6 +197,26 @@ def main():
     hbm["score_prune_frac"] = round(hbm["score_prune_GBs"] / PEAK_HBM_GBS, 4)
     hbm["quantize_frac"] = round(hbm["quantize_GBs"] / PEAK_HBM_GBS, 4)
 
+    # ---- the HBM-bound stages with all 24 layers in one launch each (no overlap: kernel rates) ----------
+    ctx.set_attend_splits(args.splits, args.splits)
+    ctx.set_overlap(0)
+    ctx.reset()
+    for f in range(W):
+        ctx.step_all_layers(packed=packed[f])
+    ctx.set_attend_timing(True)
+    for f in range(W, W + S):
+        ctx.step_all_layers(packed=packed[f])
+    n_chain, sp_ms, rq_ms = ctx.chain_times()
+    ctx.set_attend_timing(False)
+    hbm["all_layers_per_launch"] = {
+        "frames_timed": n_chain,
+        "score_prune_ms": round(sp_ms, 4), "quantize_ms": round(rq_ms, 4),
+        "score_prune_GBs": round(L * work["score_bytes"] / (sp_ms * 1e-3) / 1e9, 1),
+        "quantize_GBs": round(L * work["requant_bytes"] / (rq_ms * 1e-3) / 1e9, 1),
+    }
+    hbm["all_layers_per_launch"]["score_prune_frac"] = round(hbm["all_layers_per_launch"]["score_prune_GBs"] / PEAK_HBM_GBS, 4)
+    hbm["all_layers_per_launch"]["quantize_frac"] = round(hbm["all_layers_per_launch"]["quantize_GBs"] / PEAK_HBM_GBS, 4)
+
     # ---- the oracle on the host cores, bounded sample ------------------------------------------------
     cpu = None
     if not args.no_cpu:

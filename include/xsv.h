@@ -147,6 +147,11 @@ int xsv_set_side_cus(xsv_ctx* ctx, int compute_units);
  * few microseconds per launch; leave this off in production. */
 int xsv_set_attend_timing(xsv_ctx* ctx, int enabled);
 int xsv_attend_times(xsv_ctx* ctx, int32_t* launches, float* attend_ms, float* merge_ms, float* event_ms);
+/* With the same switch, xsv_step and xsv_step_all_layers also bracket their score + select launches and
+ * their re-quantize launch with events on the stream those run on.  Returns the number of steps recorded,
+ * the average span of the two stages in milliseconds (event cost included), and starts a new series.  In the
+ * overlapped modes the spans include whatever the attention running beside them takes away. */
+int xsv_chain_times(xsv_ctx* ctx, int32_t* steps, float* score_prune_ms, float* quantize_ms);
 /* Grid (workgroups) of the most recent attention launch of this context, 0 before the first. */
 int xsv_last_attend_workgroups(xsv_ctx* ctx, int32_t* workgroups);
 /* Tuning: workgroup shape of the attention kernel (waves x query rows per wave).  3 (default) = 8 x 64,

@@ -56,6 +56,8 @@ struct xsv_ctx {
   bool timing = false;
   std::vector<hipEvent_t> timing_events;
   size_t timing_used = 0;
+  std::vector<hipEvent_t> chain_events;  // triples on the chain's stream: before score, after select, after re-quantize
+  size_t chain_used = 0;
   int side_cus = 64;  // compute units xsv_step leaves to the prune chain while attention runs
   size_t part_rows = 0;  // rows the partial-output workspace holds
   int n_cu = 256;
@@ -99,6 +101,8 @@ void free_all(xsv_ctx* ctx) {
   for (hipEvent_t e : ctx->ev_chain) (void)hipEventDestroy(e);
   for (hipEvent_t e : ctx->timing_events) (void)hipEventDestroy(e);
   ctx->timing_events.clear();
+  for (hipEvent_t e : ctx->chain_events) (void)hipEventDestroy(e);
+  ctx->chain_events.clear();
   ctx->ev_chain.clear();
   ctx->side = nullptr;
   ctx->ev_fork = ctx->ev_join = nullptr;
@@ -465,6 +469,7 @@ int xsv_set_attend_timing(xsv_ctx* ctx, int enabled) {
   if (!ctx) return XSV_ERR_ARG;
   ctx->timing = enabled != 0;
   ctx->timing_used = 0;
+  ctx->chain_used = 0;
   return XSV_OK;
 }
 
@@ -489,6 +494,27 @@ int xsv_attend_times(xsv_ctx* ctx, int32_t* launches, float* attend_ms, float* m
   *merge_ms = n ? (float)(m / n) : 0.f;
   if (event_ms) *event_ms = n ? (float)(own / n) : 0.f;
   ctx->timing_used = 0;
+  return XSV_OK;
+}
+
+int xsv_chain_times(xsv_ctx* ctx, int32_t* steps, float* score_prune_ms, float* quantize_ms) {
+  if (!ctx || !steps || !score_prune_ms || !quantize_ms) return XSV_ERR_ARG;
+  if (ctx->broken) return XSV_ERR_HIP;
+  if (hipStreamSynchronize(ctx->stream) != hipSuccess || hipStreamSynchronize(ctx->side) != hipSuccess) return hip_fail(ctx);
+  double a = 0.0, b = 0.0;
+  const size_t n = ctx->chain_used / 3;
+  for (size_t i = 0; i < n; ++i) {
+    float t0 = 0.f, t1 = 0.f;
+    hipEvent_t* e = &ctx->chain_events[3 * i];
+    if (hipEventElapsedTime(&t0, e[0], e[1]) != hipSuccess || hipEventElapsedTime(&t1, e[1], e[2]) != hipSuccess)
+      return hip_fail(ctx);
+    a += t0;
+    b += t1;
+  }
+  *steps = (int32_t)n;
+  *score_prune_ms = n ? (float)(a / n) : 0.f;
+  *quantize_ms = n ? (float)(b / n) : 0.f;
+  ctx->chain_used = 0;
   return XSV_OK;
 }
 
@@ -547,20 +573,38 @@ static int step_layers(xsv_ctx* ctx, int layer0, int n_layers, const xsv_tensor*
     if (hipEventRecord(ctx->ev_fork, ctx->stream) != hipSuccess || hipStreamWaitEvent(ctx->side, ctx->ev_fork, 0) != hipSuccess)
       return hip_fail(ctx);
   }
+  hipEvent_t cev[3] = {nullptr, nullptr, nullptr};
+  if (ctx->timing) {
+    while (ctx->chain_events.size() < ctx->chain_used + 3) {
+      hipEvent_t e = nullptr;
+      if (hipEventCreate(&e) != hipSuccess) return hip_fail(ctx);
+      ctx->chain_events.push_back(e);
+    }
+    for (int i = 0; i < 3; ++i) cev[i] = ctx->chain_events[ctx->chain_used + i];
+    ctx->chain_used += 3;
+  }
+  hipStream_t chain = fork ? ctx->side : ctx->stream;
+  auto mark = [&](hipEvent_t e) { return !e || hipEventRecord(e, chain) == hipSuccess; };
   if (fork) {
     // the chain is enqueued first: its launches then do not queue up behind the host time of the
     // attention launches, and it starts as soon as the fork event fires
     ctx->work = ctx->side;
+    if (!mark(cev[0])) return hip_fail(ctx);
     rc = do_score_prune(ctx, layer0, n_layers, q);
+    if (!mark(cev[1])) return hip_fail(ctx);
     ctx->work = ctx->stream;
     if (rc == XSV_OK) rc = do_attend(ctx, layer0, n_layers, q, k, v, out, splits, ctx->side_cus);
     ctx->work = ctx->side;
     if (rc == XSV_OK) rc = do_quantize(ctx, layer0, n_layers, k, v);
+    if (!mark(cev[2])) return hip_fail(ctx);
     ctx->work = ctx->stream;
   } else {
     rc = do_attend(ctx, layer0, n_layers, q, k, v, out, splits, 0);
+    if (!mark(cev[0])) return hip_fail(ctx);
     if (rc == XSV_OK) rc = do_score_prune(ctx, layer0, n_layers, q);
+    if (!mark(cev[1])) return hip_fail(ctx);
     if (rc == XSV_OK) rc = do_quantize(ctx, layer0, n_layers, k, v);
+    if (!mark(cev[2])) return hip_fail(ctx);
   }
   if (fork && ctx->overlap == 2) {
     if (hipEventRecord(ctx->ev_chain[layer0], ctx->side) != hipSuccess) return hip_fail(ctx);

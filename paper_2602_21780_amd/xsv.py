@@ -42,7 +42,7 @@ class xsv_tensor(C.Structure):
 # every symbol include/xsv.h declares
 EXPORTS = (
     "xsv_create", "xsv_destroy", "xsv_reset", "xsv_dequant_attend", "xsv_score_prune", "xsv_quantize",
-    "xsv_step", "xsv_step_all_layers", "xsv_set_attend_splits", "xsv_set_attend_variant", "xsv_set_overlap", "xsv_join", "xsv_set_side_cus", "xsv_last_attend_workgroups", "xsv_set_attend_timing", "xsv_attend_times", "xsv_cache_len", "xsv_cache_export",
+    "xsv_step", "xsv_step_all_layers", "xsv_set_attend_splits", "xsv_set_attend_variant", "xsv_set_overlap", "xsv_join", "xsv_set_side_cus", "xsv_last_attend_workgroups", "xsv_set_attend_timing", "xsv_attend_times", "xsv_chain_times", "xsv_cache_len", "xsv_cache_export",
     "xsv_cache_import", "xsv_last_selection", "xsv_quantize_k", "xsv_quantize_v", "xsv_score",
     "xsv_topk_keep", "xsv_strerror",
 )
@@ -75,6 +75,7 @@ def lib():
         L.xsv_set_side_cus.argtypes = [vp, i32]
         L.xsv_last_attend_workgroups.argtypes = [vp, C.POINTER(C.c_int32)]
         L.xsv_set_attend_timing.argtypes = [vp, i32]
+        L.xsv_chain_times.argtypes = [vp, C.POINTER(C.c_int32), C.POINTER(C.c_float), C.POINTER(C.c_float)]
         L.xsv_attend_times.argtypes = [vp, C.POINTER(C.c_int32), C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_float)]
         L.xsv_cache_len.argtypes = [vp, i32, C.POINTER(C.c_int32)]
         L.xsv_cache_export.argtypes = [vp, i32] + [vp] * 10
@@ -186,6 +187,12 @@ class Context:
         n, a, m, e = C.c_int32(), C.c_float(), C.c_float(), C.c_float()
         _check(lib().xsv_attend_times(self._h, C.byref(n), C.byref(a), C.byref(m), C.byref(e)), "xsv_attend_times")
         return n.value, a.value, m.value, e.value
+
+    def chain_times(self):
+        """(steps, score + select span ms, re-quantize span ms), averages since the last call."""
+        n, a, b = C.c_int32(), C.c_float(), C.c_float()
+        _check(lib().xsv_chain_times(self._h, C.byref(n), C.byref(a), C.byref(b)), "xsv_chain_times")
+        return n.value, a.value, b.value
 
     def last_attend_workgroups(self) -> int:
         w = C.c_int32()
