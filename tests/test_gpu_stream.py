@@ -314,6 +314,8 @@ def test_attention_timing_series():
         ctx.step(0, q[0], k[0], v[0])
     launches, attend_ms, merge_ms, event_ms = ctx.attend_times()
     assert launches == 4 and attend_ms > 0.0 and merge_ms > 0.0 and event_ms > 0.0
+    steps, score_prune_ms, quantize_ms = ctx.chain_times()
+    assert steps == 4 and score_prune_ms > 0.0 and quantize_ms > 0.0
     assert ctx.attend_times()[0] == 0                      # a call starts a new series
     ctx.set_attend_timing(False)
     q, k, v = src.frame(4)
