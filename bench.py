@@ -55,7 +55,7 @@ def main():
     ap.add_argument("--overlap", type=int, choices=[0, 1, 2], default=2,
                     help="0: prune chain after attention on one stream; 1: on a side stream, joined per call; "
                          "2: side stream, joined lazily (once per frame here)")
-    ap.add_argument("--side-cus", type=int, default=-1, help="compute units left to the overlapped prune chain (-1 = library default)")
+    ap.add_argument("--side-cus", type=int, default=-2, help="compute units left to the overlapped prune chain (-2 = library default, -1 = by launch size)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain streaming kernel of known size (1 GiB read + 1 GiB written, 4 times), the yardstick "
                          "for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -86,7 +86,7 @@ def main():
     ctx = xsv.Context.from_spec(spec)
     ctx.set_attend_splits(args.splits, args.splits)
     ctx.set_overlap(args.overlap)
-    if args.side_cus >= 0:
+    if args.side_cus >= -1:
         ctx.set_side_cus(args.side_cus)
     packed = [ctx.pack_layers(q, k, v, out) for (q, k, v) in frames]
     torch.cuda.synchronize()

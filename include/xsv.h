@@ -134,8 +134,9 @@ int xsv_set_overlap(xsv_ctx* ctx, int mode);
  * unless overlap mode 2 has steps outstanding. */
 int xsv_join(xsv_ctx* ctx);
 /* Tuning: compute units the attention launch of xsv_step / xsv_step_all_layers leaves free for the
- * overlapped score/select/re-quantize chain (default 64; 0 .. half the chip).  Without spare units
- * the chain only starts when attention drains.  Ignored when overlap is off or splits are fixed. */
+ * overlapped score/select/re-quantize chain (0 .. half the chip).  Without spare units the chain only
+ * starts when attention drains.  -1 (default) = a quarter of the chip, an eighth when the attention launch
+ * is long (more than about 24 key tiles per workgroup).  Ignored when overlap is off or splits are fixed. */
 int xsv_set_side_cus(xsv_ctx* ctx, int compute_units);
 /* Measurement aid.  While enabled, every attention launch of this context (xsv_dequant_attend, xsv_step,
  * xsv_step_all_layers) is bracketed by events on the context's stream: before the attention kernel,

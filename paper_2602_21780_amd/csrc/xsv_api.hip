@@ -58,7 +58,7 @@ struct xsv_ctx {
   size_t timing_used = 0;
   std::vector<hipEvent_t> chain_events;  // triples on the chain's stream: before score, after select, after re-quantize
   size_t chain_used = 0;
-  int side_cus = 64;  // compute units xsv_step leaves to the prune chain while attention runs
+  int side_cus = -1;  // compute units xsv_step leaves to the prune chain while attention runs (-1: by launch size)
   size_t part_rows = 0;  // rows the partial-output workspace holds
   int n_cu = 256;
   bool broken = false;
@@ -525,7 +525,7 @@ int xsv_last_attend_workgroups(xsv_ctx* ctx, int32_t* workgroups) {
 }
 
 int xsv_set_side_cus(xsv_ctx* ctx, int compute_units) {
-  if (!ctx || compute_units < 0 || compute_units > ctx->n_cu / 2) return XSV_ERR_ARG;
+  if (!ctx || compute_units < -1 || compute_units > ctx->n_cu / 2) return XSV_ERR_ARG;
   ctx->side_cus = compute_units;
   return XSV_OK;
 }
@@ -593,7 +593,22 @@ static int step_layers(xsv_ctx* ctx, int layer0, int n_layers, const xsv_tensor*
     rc = do_score_prune(ctx, layer0, n_layers, q);
     if (!mark(cev[1])) return hip_fail(ctx);
     ctx->work = ctx->stream;
-    if (rc == XSV_OK) rc = do_attend(ctx, layer0, n_layers, q, k, v, out, splits, ctx->side_cus);
+    if (rc == XSV_OK) {
+      // The chain takes about the same time whatever the attention launch takes, so the longer the
+      // attention, the smaller the share of the chip worth leaving to it: a quarter of the compute units
+      // up to about 24 key tiles per attention workgroup, an eighth beyond.
+      int spare = ctx->side_cus;
+      if (spare < 0) {
+        const xsv_config& c = ctx->cfg;
+        const int rows = attend_rows_per_workgroup(ctx->attend_variant);
+        const long long units = (long long)((c.tokens_per_frame + rows - 1) / rows) * c.n_heads * n_layers;
+        const long long tiles = (ctx->layers[layer0].T + kTile - 1) / kTile + (c.tokens_per_frame + kTile - 1) / kTile;
+        const int per_cu = ctx->attend_variant >= 2 ? 1 : 2;
+        const long long wgs = (long long)per_cu * (ctx->n_cu - ctx->n_cu / 4);
+        spare = units * tiles > 24 * wgs ? ctx->n_cu / 8 : ctx->n_cu / 4;
+      }
+      rc = do_attend(ctx, layer0, n_layers, q, k, v, out, splits, spare);
+    }
     ctx->work = ctx->side;
     if (rc == XSV_OK) rc = do_quantize(ctx, layer0, n_layers, k, v);
     if (!mark(cev[2])) return hip_fail(ctx);
