@@ -59,13 +59,13 @@ __device__ __forceinline__ int tau(int i) {
   return 16 * (a >> 1) + 8 * ((i >> 2) & 1) + 4 * (a & 1) + (i & 3);
 }
 
-// Eight consecutive codes as floats: the whole dword at 4 bits, half `sel` of it at 2 bits.
-// (The masked words pass through an opaque move: the optimizer would otherwise fold the masks into one
-// bit-field extract PER code in front of each conversion instead of the byte-select conversions.)
+// code e (0 .. 32/BITS-1) of a packed dword as float; the masks are shared between neighbours
 template <int BITS>
-__device__ __forceinline__ void unpack_codes8(uint32_t w, int sel, float* out) {
+__device__ __forceinline__ void unpack_codes(uint32_t w, float* out) {
   if constexpr (BITS == 4) {
     uint32_t t0 = w & 0x0f0f0f0fu, t1 = (w >> 4) & 0x0f0f0f0fu;
+    // (opaque to the optimizer, which would otherwise fold the masks into one bit-field extract
+    // PER code in front of each conversion instead of the byte-select conversions below)
     asm volatile("" : "+v"(t0), "+v"(t1));
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
@@ -73,38 +73,40 @@ __device__ __forceinline__ void unpack_codes8(uint32_t w, int sel, float* out) {
       out[2 * b + 1] = (float)((t1 >> (8 * b)) & 0xffu);
     }
   } else {
-    const uint32_t h = w >> (16 * sel);  // codes 0..7 of this half: bits 2e .. 2e+1
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      uint32_t t = (h >> (2 * i)) & 0x0303u;
+      uint32_t t = (w >> (2 * i)) & 0x03030303u;
       asm volatile("" : "+v"(t));
-      out[i] = (float)(t & 0xffu);
-      out[4 + i] = (float)((t >> 8) & 0xffu);
+#pragma unroll
+      for (int b = 0; b < 4; ++b) out[4 * b + i] = (float)((t >> (8 * b)) & 0xffu);
     }
   }
 }
 
 // ---- staging of one key tile -------------------------------------------------------------------
-// A tile is 64 tokens x 64 channels of K and of V, cut into 512 "items" of 8 elements per role (one
-// dword of 4-bit codes, half a dword of 2-bit codes, 16 bytes of bf16).  The first half of the
-// workgroup's threads stages K, the second half V; both run the SAME code on different pointers,
-// because the packed layouts mirror each other:  K item = (token row, channel run of 8) with
-// per-channel parameters,  V item = (channel row, token run of 8) with per-token parameters, and the
-// LDS tile of either is [row][column run].  The NH threads of a role are split in two halves, one per
-// 32 rows of the tile; a thread stages the items (row0 + it * kRowStep, run) of its half, so all its
-// items share the column run and — also with groups of 32 — the parameters.
+// A tile is 64 tokens x 64 channels of K and of V.  It is cut into "items" of one dword of codes
+// (8 or 16 elements; bf16 tiles: 16 bytes = 8 elements).  The first half of the workgroup's threads
+// stages K, the second half V; both run the SAME code on different pointers, because the packed
+// layouts mirror each other:  K item i = (token i / RI, channel run i % RI) with per-channel
+// parameters,  V item i = (channel i / RI, token run i % RI) with per-token parameters, and the
+// LDS tile of either is [row = i / RI][column run].  A thread stages items u, u + NH, .. (u = its
+// index within its half, NH threads per half); NH is a multiple of RI, so all its items share the
+// column run and (within a group) the parameters.
 template <int BITS, int G, int NH>
 struct Stage {
   static constexpr bool kQuant = BITS != 16;
-  static constexpr int kPer = 8;                          // elements per item
-  static constexpr int kRI = kD / kPer;                   // items per row (8)
-  static constexpr int kIter = (kTile * kRI) / NH;        // items per thread
-  static constexpr int kRowStep = (NH / 2) / kRI;         // rows between a thread's consecutive items
-  static constexpr int kRowDw = kD * BITS / 32;           // dwords per packed row
-  static_assert((kTile * kRI) % NH == 0 && (NH / 2) % kRI == 0 && kRowStep * kIter == 32, "thread count must tile the items");
+  static constexpr int kPer = kQuant ? 32 / BITS : 8;  // elements per item
+  static constexpr int kRI = kD / kPer;                 // items per row
+  static constexpr int kItems = kTile * kRI;            // per tile and role
+  static constexpr int kIter = kItems / NH;             // items per thread
+  static constexpr int kRowStep = NH / kRI;             // rows between a thread's consecutive items
+  // parameter sets per thread: with G = 32 the rows < 32 and >= 32 of a tile are different groups
+  static constexpr int kSets = (G >= 64 || kIter == 1) ? 1 : 2;
+  static_assert(kItems % NH == 0 && NH % kRI == 0, "thread count must tile the items");
+  static_assert(kSets == 1 || (kIter % 2 == 0 && kRowStep * (kIter / 2) == 32), "two groups need an even split");
 
   uint32_t code[kQuant ? kIter : 1];
-  float ps[kQuant ? kPer : 1], pz[kQuant ? kPer : 1];
+  float ps[kQuant ? kSets : 1][kPer], pz[kQuant ? kSets : 1][kPer];
   uint4 row[kQuant ? 1 : kIter];  // bf16 cache
 };
 
@@ -119,38 +121,39 @@ struct RolePtrs {      // what distinguishes the K half from the V half
 template <int BITS, int G, int NH>
 __device__ __forceinline__ void fetch_cache_tile(Stage<BITS, G, NH>& st, const RolePtrs& rp, int Tcap, int tile, int u) {
   using S = Stage<BITS, G, NH>;
-  const int half = u / (NH / 2), w = u % (NH / 2);
-  const int row0 = 32 * half + w / S::kRI, o = w % S::kRI;  // first row and column run of this thread
-  const uint32_t* base = rp.codes + (size_t)tile * kTile * S::kRowDw;
+  constexpr int kRowDw = kD * BITS / 32;  // dwords per K row == dwords per V block row
+  const uint32_t* base = rp.codes + (size_t)tile * kTile * kRowDw;
   if constexpr (!S::kQuant) {
 #pragma unroll
-    for (int it = 0; it < S::kIter; ++it)
-      st.row[it] = reinterpret_cast<const uint4*>(base)[(row0 + it * S::kRowStep) * S::kRI + o];
+    for (int it = 0; it < S::kIter; ++it) st.row[it] = reinterpret_cast<const uint4*>(base)[u + it * NH];
   } else {
-    // 4 bits: dword o of the row; 2 bits: dword o/2, whose half o%2 holds the run
-    const int dw = BITS == 4 ? o : o >> 1;
 #pragma unroll
-    for (int it = 0; it < S::kIter; ++it) st.code[it] = base[(row0 + it * S::kRowStep) * S::kRowDw + dw];
-    // K: parameters [group][channel], the run's channels o*8.. of the group holding the thread's rows
-    // V: parameters [token][channel group], the run's tokens o*8.. of the channel group holding its rows
-    const int sub = G >= kTile ? 0 : half;  // 32-row half of the tile = group index within it
-    const float *ps, *pz;
-    size_t stride;
-    if (!rp.is_v) {
-      const size_t g = (G >= kTile) ? (size_t)tile / (G / kTile) : (size_t)tile * (kTile / G) + sub;
-      ps = rp.ps + g * kD + o * S::kPer;
-      pz = rp.pz + g * kD + o * S::kPer;
-      stride = 1;
-    } else {
-      const size_t t0 = (size_t)tile * kTile + o * S::kPer;
-      ps = rp.ps + t0 * (kD / G) + sub;
-      pz = rp.pz + t0 * (kD / G) + sub;
-      stride = kD / G;
-    }
+    for (int it = 0; it < S::kIter; ++it) st.code[it] = base[u + it * NH];
+    const int o = u % S::kRI;
 #pragma unroll
-    for (int e = 0; e < S::kPer; ++e) {
-      st.ps[e] = ps[e * stride];
-      st.pz[e] = pz[e * stride];
+    for (int set0 = 0; set0 < S::kSets; ++set0) {
+      // 32-row half of the tile this set belongs to (a thread with a single item has a single row)
+      const int set = (G >= 64) ? 0 : (S::kIter == 1 ? (u / S::kRI) / 32 : set0);
+      // K: parameters [group][channel], the item's channels are o*kPer.. of group (tile, set)
+      // V: parameters [token][channel group], the item's tokens are o*kPer.. of channel group `set`
+      const float *ps, *pz;
+      size_t stride;
+      if (!rp.is_v) {
+        const size_t g = (G >= kTile) ? (size_t)tile / (G / kTile) : (size_t)tile * (kTile / G) + set;
+        ps = rp.ps + g * kD + o * S::kPer;
+        pz = rp.pz + g * kD + o * S::kPer;
+        stride = 1;
+      } else {
+        const size_t t0 = (size_t)tile * kTile + o * S::kPer;
+        ps = rp.ps + t0 * (kD / G) + set;
+        pz = rp.pz + t0 * (kD / G) + set;
+        stride = kD / G;
+      }
+#pragma unroll
+      for (int e = 0; e < S::kPer; ++e) {
+        st.ps[set0][e] = ps[e * stride];
+        st.pz[set0][e] = pz[e * stride];
+      }
     }
   }
 }
@@ -158,29 +161,34 @@ __device__ __forceinline__ void fetch_cache_tile(Stage<BITS, G, NH>& st, const R
 template <int BITS, int G, int NH>
 __device__ __forceinline__ void store_cache_tile(const Stage<BITS, G, NH>& st, uint16_t* lds, int u) {
   using S = Stage<BITS, G, NH>;
-  const int half = u / (NH / 2), w = u % (NH / 2);
-  const int row0 = 32 * half + w / S::kRI, o = w % S::kRI;
+  const int r0 = u / S::kRI, o = u % S::kRI;
   // (code - zero) * scale as one fused multiply-add per element: code * scale + (-zero * scale).
   // It differs from the cache's canonical two-step value by at most one fp32 rounding of
   // zero * scale, far below the bf16 rounding that follows.
-  float nzs[S::kQuant ? S::kPer : 1];
+  float nzs[S::kQuant ? S::kSets : 1][S::kPer];
   if constexpr (S::kQuant) {
 #pragma unroll
-    for (int e = 0; e < S::kPer; ++e) nzs[e] = -st.pz[e] * st.ps[e];
+    for (int set = 0; set < S::kSets; ++set)
+#pragma unroll
+      for (int e = 0; e < S::kPer; ++e) nzs[set][e] = -st.pz[set][e] * st.ps[set][e];
   }
 #pragma unroll
   for (int it = 0; it < S::kIter; ++it) {
-    uint16_t* dst = lds + (row0 + it * S::kRowStep) * kLdsStride + o * S::kPer;
+    uint16_t* dst = lds + (r0 + it * S::kRowStep) * kLdsStride + o * S::kPer;
     if constexpr (!S::kQuant) {
       *reinterpret_cast<uint4*>(dst) = st.row[it];
     } else {
+      const int set = (S::kSets == 1) ? 0 : (it >= S::kIter / 2);
       float f[S::kPer];
-      unpack_codes8<BITS>(st.code[it], o & 1, f);
+      unpack_codes<BITS>(st.code[it], f);
       uint32_t pk[S::kPer / 2];
 #pragma unroll
       for (int e = 0; e < S::kPer; e += 2)
-        pk[e / 2] = pack_bf16(__builtin_fmaf(f[e], st.ps[e], nzs[e]), __builtin_fmaf(f[e + 1], st.ps[e + 1], nzs[e + 1]));
-      *reinterpret_cast<uint4*>(dst) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+        pk[e / 2] = pack_bf16(__builtin_fmaf(f[e], st.ps[set][e], nzs[set][e]),
+                              __builtin_fmaf(f[e + 1], st.ps[set][e + 1], nzs[set][e + 1]));
+#pragma unroll
+      for (int w = 0; w < S::kPer / 8; ++w)
+        *reinterpret_cast<uint4*>(dst + w * 8) = make_uint4(pk[4 * w], pk[4 * w + 1], pk[4 * w + 2], pk[4 * w + 3]);
     }
   }
 }
