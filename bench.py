@@ -23,10 +23,10 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X dense bf16
 PEAK_HBM_GBS = 8000.0
-# HBM bytes of one attend_kernel launch of this workload (fetch 25.2 MB + write 20.1 MB), from the two
+# HBM bytes of one attend_kernel launch of this workload (fetch 30.3 MB + write 25.7 MB), from the two
 # rocprofv3 --pmc runs summarized in profiles/attend_cfg2_hbm_traffic.md; not measurable from inside this
 # process, so it is carried here and only reported for the grid it was measured on.
-TRAFFIC_ATTEND_CFG2 = {"workgroups": 192, "bytes": 45.4e6}
+TRAFFIC_ATTEND_CFG2 = {"workgroups": 240, "bytes": 56.0e6}
 
 
 def algorithmic_work(spec, Tc, Tn, P):

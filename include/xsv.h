@@ -138,6 +138,10 @@ int xsv_join(xsv_ctx* ctx);
  * starts when attention drains.  -1 (default) = a quarter of the chip, an eighth when the attention launch
  * is long (more than about 24 key tiles per workgroup).  Ignored when overlap is off or splits are fixed. */
 int xsv_set_side_cus(xsv_ctx* ctx, int compute_units);
+/* Tuning: in xsv_step / xsv_step_all_layers with overlap, cut every (head, query block) into one more key
+ * range than the spare units allow, the extra one `percent` of a full range long (1..100; 0 = off): its
+ * workgroups end early and hand their compute units to the chain for the rest of the attention launch. */
+int xsv_set_short_range(xsv_ctx* ctx, int percent);
 /* Measurement aid.  While enabled, every attention launch of this context (xsv_dequant_attend, xsv_step,
  * xsv_step_all_layers) is bracketed by events on the context's stream: before the attention kernel,
  * between it and the kernel that merges key-range partials, after, and once more right behind.

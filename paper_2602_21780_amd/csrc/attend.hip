@@ -327,9 +327,17 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
     const int g = (slot / nqb) * 8 + xcd;  // (layer, head, key range) triple
     wg = ((g / a.xcd_ranges) * nqb + slot % nqb) * a.xcd_ranges + g % a.xcd_ranges;
   }
-  const long long piece_end = part.begin(wg + 1);
+  // start of workgroup w's piece on the (unit, tile) line; with `long_len` every unit is cut into
+  // equal_ranges - 1 ranges of long_len tiles and a last, shorter one (its workgroup ends early and
+  // leaves its compute unit to the kernels that run beside this one)
+  auto piece_begin = [&](int w) -> long long {
+    if (a.long_len <= 0) return part.begin(w);
+    const int un = w / a.equal_ranges, p = w % a.equal_ranges;
+    return (long long)un * part.n_tiles + min(p * a.long_len, part.n_tiles);
+  };
+  const long long piece_end = piece_begin(wg + 1);
 
-  for (long long pos = part.begin(wg); pos < piece_end;) {
+  for (long long pos = piece_begin(wg); pos < piece_end;) {
   const int unit = part.unit_of(pos);
   const int t_begin = (int)(pos - (long long)unit * part.n_tiles);
   const int t_end = (int)min((long long)part.n_tiles, t_begin + (piece_end - pos));
@@ -581,7 +589,7 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
       // fp32).  Lane (j, hh) owns 32 channels of row j, in register order o0[0..15], o1[0..15], as
       // four 16-byte pieces i; a block of 32 rows is stored [i][hh][j], so that every store
       // instruction of the wave covers 1 KB of consecutive memory.
-      const int piece = wg - part.first_wg(unit);
+      const int piece = a.equal_ranges > 0 ? wg % a.equal_ranges : wg - part.first_wg(unit);
       const int nblk = (n + 31) / 32;
       const size_t row = (((size_t)piece * a.b.n_layers + lb) * H + h) * n + q_row;
       const size_t blk = (((size_t)piece * a.b.n_layers + lb) * H + h) * nblk + (q_row >> 5);

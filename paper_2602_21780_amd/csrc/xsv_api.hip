@@ -58,6 +58,7 @@ struct xsv_ctx {
   size_t timing_used = 0;
   std::vector<hipEvent_t> chain_events;  // triples on the chain's stream: before score, after select, after re-quantize
   size_t chain_used = 0;
+  int short_pct = 35; // xsv_step: length of one extra, short key range per unit, in percent of a long one (0 = none)
   int side_cus = -1;  // compute units xsv_step leaves to the prune chain while attention runs (-1: by launch size)
   size_t part_rows = 0;  // rows the partial-output workspace holds
   int n_cu = 256;
@@ -205,7 +206,23 @@ int do_attend(xsv_ctx* ctx, int layer0, int n_layers, const xsv_tensor* q, const
   a.Tc = ctx->layers[layer0].T;
   a.n = ctx->cfg.tokens_per_frame;
   a.variant = ctx->attend_variant;
-  const AttendPlan plan = choose_grid(ctx, n_layers, a.Tc, splits_req, spare_cus);
+  AttendPlan plan = choose_grid(ctx, n_layers, a.Tc, splits_req, spare_cus);
+  a.long_len = 0;
+  if (splits_req <= 0 && spare_cus > 0 && ctx->short_pct > 0) {
+    // beside the overlapped chain: the equal cut that leaves spare units, plus one short range per unit
+    const int rows = attend_rows_per_workgroup(ctx->attend_variant);
+    const int n_units = ((a.n + rows - 1) / rows) * ctx->cfg.n_heads * n_layers;
+    const int n_tiles = (a.Tc + kTile - 1) / kTile + (a.n + kTile - 1) / kTile;
+    const int S = plan.n_wgs % n_units == 0 ? plan.n_wgs / n_units : 0;
+    if (S >= 1 && (S + 1) * n_units <= ctx->n_cu - 8 && S + 1 <= kMaxPieces) {
+      const AttendPlan more = plan_attend(ctx->attend_variant, n_layers, ctx->cfg.n_heads, a.n, a.Tc, (S + 1) * n_units, ctx->part_rows);
+      const int len = (100 * n_tiles + 100 * S + ctx->short_pct - 1) / (100 * S + ctx->short_pct);
+      if (more.n_wgs == (S + 1) * n_units && len * S < n_tiles) {
+        plan = more;
+        a.long_len = len;
+      }
+    }
+  }
   a.n_wgs = plan.n_wgs;
   a.rows_wg = plan.rows_wg;
   a.cut = plan.max_pieces > 1;
@@ -521,6 +538,12 @@ int xsv_chain_times(xsv_ctx* ctx, int32_t* steps, float* score_prune_ms, float* 
 int xsv_last_attend_workgroups(xsv_ctx* ctx, int32_t* workgroups) {
   if (!ctx || !workgroups) return XSV_ERR_ARG;
   *workgroups = ctx->last_attend_wgs;
+  return XSV_OK;
+}
+
+int xsv_set_short_range(xsv_ctx* ctx, int percent) {
+  if (!ctx || percent < 0 || percent > 100) return XSV_ERR_ARG;
+  ctx->short_pct = percent;
   return XSV_OK;
 }
 

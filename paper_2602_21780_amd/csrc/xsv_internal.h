@@ -105,6 +105,7 @@ struct AttendArgs {
   int rows_wg;   // query rows per workgroup of this variant
   int cut;       // some unit is shared by several workgroups: partials are written and merged
   int equal_ranges;  // > 0: every unit is cut into exactly this many key ranges
+  int long_len;      // > 0 (with equal_ranges): tiles of each range but the last, which takes the rest
   int xcd_ranges;  // > 0: every unit is cut into this many key ranges and the grid is permuted for L2 sharing
   float qscale;  // softmax scale * log2(e)
 };

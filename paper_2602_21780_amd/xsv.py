@@ -42,7 +42,7 @@ class xsv_tensor(C.Structure):
 # every symbol include/xsv.h declares
 EXPORTS = (
     "xsv_create", "xsv_destroy", "xsv_reset", "xsv_dequant_attend", "xsv_score_prune", "xsv_quantize",
-    "xsv_step", "xsv_step_all_layers", "xsv_set_attend_splits", "xsv_set_attend_variant", "xsv_set_overlap", "xsv_join", "xsv_set_side_cus", "xsv_last_attend_workgroups", "xsv_set_attend_timing", "xsv_attend_times", "xsv_chain_times", "xsv_cache_len", "xsv_cache_export",
+    "xsv_step", "xsv_step_all_layers", "xsv_set_attend_splits", "xsv_set_attend_variant", "xsv_set_overlap", "xsv_join", "xsv_set_side_cus", "xsv_set_short_range", "xsv_last_attend_workgroups", "xsv_set_attend_timing", "xsv_attend_times", "xsv_chain_times", "xsv_cache_len", "xsv_cache_export",
     "xsv_cache_import", "xsv_last_selection", "xsv_quantize_k", "xsv_quantize_v", "xsv_score",
     "xsv_topk_keep", "xsv_strerror",
 )
@@ -73,6 +73,7 @@ def lib():
         L.xsv_set_attend_variant.argtypes = [vp, i32]
         L.xsv_set_overlap.argtypes = [vp, i32]
         L.xsv_set_side_cus.argtypes = [vp, i32]
+        L.xsv_set_short_range.argtypes = [vp, i32]
         L.xsv_last_attend_workgroups.argtypes = [vp, C.POINTER(C.c_int32)]
         L.xsv_set_attend_timing.argtypes = [vp, i32]
         L.xsv_chain_times.argtypes = [vp, C.POINTER(C.c_int32), C.POINTER(C.c_float), C.POINTER(C.c_float)]
@@ -201,6 +202,9 @@ class Context:
 
     def join(self):
         _check(lib().xsv_join(self._h), "xsv_join")
+
+    def set_short_range(self, percent):
+        _check(lib().xsv_set_short_range(self._h, int(percent)), "xsv_set_short_range")
 
     def set_side_cus(self, compute_units):
         _check(lib().xsv_set_side_cus(self._h, int(compute_units)), "xsv_set_side_cus")

@@ -63,6 +63,7 @@ def test_null_context_is_rejected(lib):
     assert lib.xsv_join(None) == xsv.XSV_ERR_ARG
     assert lib.xsv_set_overlap(None, 1) == xsv.XSV_ERR_ARG
     assert lib.xsv_set_side_cus(None, 0) == xsv.XSV_ERR_ARG
+    assert lib.xsv_set_short_range(None, 0) == xsv.XSV_ERR_ARG
     assert lib.xsv_set_attend_timing(None, 1) == xsv.XSV_ERR_ARG
     assert lib.xsv_attend_times(None, None, None, None, None) == xsv.XSV_ERR_ARG
     assert lib.xsv_chain_times(None, None, None, None) == xsv.XSV_ERR_ARG

@@ -12,10 +12,12 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-def run_stream(spec, frames, rows=None, splits=0, **over):
+def run_stream(spec, frames, rows=None, splits=0, short=None, **over):
     ctx, st = parity.make_pair(spec, **over)
     if splits:
         ctx.set_attend_splits(splits, splits)
+    if short is not None:
+        ctx.set_short_range(short)
     src = FrameSource(spec, DEV)
     worst = (0.0, 0.0)
     ties = 0
@@ -48,6 +50,13 @@ def test_mid_size_streams_all_code_widths(bits, G):
     spec = CONFIGS[0].with_(name=f"mid-b{bits}-g{G}", n_heads=3, tokens_per_frame=200, budget=700, kv_bits=bits,
                             group_size=G, n_layers=2, seed=11)
     run_stream(spec, 6)
+
+
+@pytest.mark.parametrize("short", [0, 10, 60, 100])
+def test_short_extra_key_range(short):
+    """The overlapped step's cut with one shorter key range per (head, query block), at several lengths."""
+    spec = CONFIGS[0].with_(name=f"short{short}", n_heads=2, tokens_per_frame=200, budget=1500, n_layers=2, seed=13)
+    run_stream(spec, 10, short=short)
 
 
 def test_budget_below_two_frames_keeps_first_and_current():
