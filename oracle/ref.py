@@ -33,7 +33,7 @@ class _Config(C.Structure):
         ("n_layers", C.c_int32), ("n_heads", C.c_int32), ("head_dim", C.c_int32),
         ("tokens_per_frame", C.c_int32), ("n_special", C.c_int32), ("budget", C.c_int32),
         ("kv_bits", C.c_int32), ("group_size", C.c_int32), ("pool_size", C.c_int32),
-        ("softmax_scale", C.c_float),
+        ("softmax_scale", C.c_float), ("score_mode", C.c_int32),
     ]
 
 
@@ -47,6 +47,8 @@ def lib():
         _lib.xsv_ref_create.restype = C.c_void_p
         _lib.xsv_ref_create.argtypes = [C.POINTER(_Config)]
         _lib.xsv_ref_destroy.argtypes = [C.c_void_p]
+        _lib.xsv_ref_num_sets.argtypes = [C.c_void_p]
+        _lib.xsv_ref_num_sets.restype = C.c_int
         for name in ("xsv_ref_cache_len", "xsv_ref_last_scores_len", "xsv_ref_last_keep_len"):
             getattr(_lib, name).argtypes = [C.c_void_p, C.c_int]
             getattr(_lib, name).restype = C.c_int
@@ -175,9 +177,9 @@ class RefStream:
     """One oracle stream: `n_layers` independent caches stepped frame by frame."""
 
     def __init__(self, n_layers, n_heads, head_dim, tokens_per_frame, n_special, budget, kv_bits,
-                 group_size, pool_size=16, softmax_scale=0.0):
+                 group_size, pool_size=16, softmax_scale=0.0, score_mode=0):
         self.cfg = _Config(n_layers, n_heads, head_dim, tokens_per_frame, n_special, budget, kv_bits,
-                           group_size, pool_size, softmax_scale)
+                           group_size, pool_size, softmax_scale, score_mode)
         self._h = lib().xsv_ref_create(C.byref(self.cfg))
         if not self._h:
             raise ValueError("xsv_ref_create rejected the configuration")
@@ -195,11 +197,17 @@ class RefStream:
         s = self.cfg.softmax_scale
         return s if s != 0.0 else 1.0 / np.sqrt(self.cfg.head_dim)
 
+    @property
+    def sets(self):
+        """Index sets per layer: 1, or one per head when score_mode is 1."""
+        return lib().xsv_ref_num_sets(self._h)
+
     def cache_len(self, layer=0):
         return lib().xsv_ref_cache_len(self._h, layer)
 
     def step(self, layer, q, k_new, v_new, rows=None, attend=True, forced_keep=None):
-        """Returns (out fp32 [H][n_rows][d] or None, new cache length)."""
+        """Returns (out fp32 [H][n_rows][d] or None, new cache length).
+        forced_keep: [T'] (one index set per layer) or [sets][T']."""
         q, k_new, v_new = _u16(q), _u16(k_new), _u16(v_new)
         H, n, d = self.cfg.n_heads, self.cfg.tokens_per_frame, self.cfg.head_dim
         assert q.shape == (H, n, d) and k_new.shape == (H, n, d) and v_new.shape == (H, n, d)
@@ -213,9 +221,9 @@ class RefStream:
         else:
             rows = None
         if forced_keep is not None:
-            forced_keep = np.ascontiguousarray(forced_keep, np.int32)
+            forced_keep = np.ascontiguousarray(forced_keep, np.int32).reshape(self.sets, -1)
         T = lib().xsv_ref_step(self._h, layer, _p(q), _p(k_new), _p(v_new), _p(rows), n_rows, _p(out),
-                               _p(forced_keep), 0 if forced_keep is None else len(forced_keep))
+                               _p(forced_keep), 0 if forced_keep is None else forced_keep.shape[1])
         if T < 0:
             raise ValueError(f"xsv_ref_step failed ({T})")
         return out, T
@@ -242,10 +250,12 @@ class RefStream:
         vz = np.zeros((H, T, d // G), np.float32) if quant else None
         kb = None if quant else np.zeros((H, T, d), np.uint16)
         vb = None if quant else np.zeros((H, T, d), np.uint16)
-        tf = np.zeros(T, np.int32)
-        ti = np.zeros(T, np.int32)
-        sc = np.zeros(lib().xsv_ref_last_scores_len(self._h, layer), np.float32)
-        kp = np.zeros(lib().xsv_ref_last_keep_len(self._h, layer), np.int32)
+        # one index set per layer: 1-D arrays; one per head (score_mode 1): a leading axis of H sets
+        lead = () if self.sets == 1 else (self.sets,)
+        tf = np.zeros(lead + (T,), np.int32)
+        ti = np.zeros(lead + (T,), np.int32)
+        sc = np.zeros(lead + (lib().xsv_ref_last_scores_len(self._h, layer),), np.float32)
+        kp = np.zeros(lead + (lib().xsv_ref_last_keep_len(self._h, layer),), np.int32)
         lib().xsv_ref_export(self._h, layer, _p(kc), _p(ks), _p(kz), _p(vc), _p(vs), _p(vz), _p(kb), _p(vb),
                              _p(tf), _p(ti), _p(sc), _p(kp))
         return RefCache(T, kc, ks, kz, vc, vs, vz, kb, vb, tf, ti, sc, kp)

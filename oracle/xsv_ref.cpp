@@ -324,17 +324,24 @@ struct xsv_ref_config {
   int32_t group_size;  // G
   int32_t pool_size;   // g
   float softmax_scale;  // 0 → 1/sqrt(head_dim)
+  // 0: the paper's score (Sec. 3.2: queries and keys averaged over the heads, ONE retained index set
+  //    per layer, shared by all heads).
+  // 1: a variant, not the paper's: the head averages are left out, every head scores its own keys
+  //    with its own pooled queries and keeps its own top-k.  All heads still keep the same NUMBER of
+  //    tokens, so the cache length stays one number per layer.
+  int32_t score_mode;
 };
 
+// "sets" below = index sets per layer: 1 (score_mode 0) or H (score_mode 1, set s belongs to head s).
 struct RefLayer {
   int T = 0, T_first = 0, frames = 0;
   std::vector<uint8_t> k_codes, v_codes;        // [H][T][d]
   std::vector<float> k_scale, k_zero;           // [H][ceil(T/G)][d]
   std::vector<float> v_scale, v_zero;           // [H][T][d/G]
   std::vector<uint16_t> k_bf16, v_bf16;         // [H][T][d] when kv_bits == 16
-  std::vector<int32_t> token_frame, token_index;  // [T]
-  std::vector<float> last_scores;               // [P] of the last step that scored
-  std::vector<int32_t> last_keep;               // positions in [cache ; frame] kept by the last step
+  std::vector<int32_t> token_frame, token_index;  // [sets][T]
+  std::vector<float> last_scores;               // [sets][P] of the last step that scored
+  std::vector<int32_t> last_keep;               // [sets][T'] positions in [cache ; frame] kept by the last step
 };
 
 struct xsv_ref_state {
@@ -346,6 +353,7 @@ xsv_ref_state* xsv_ref_create(const xsv_ref_config* cfg) {
   if (!cfg || cfg->n_layers <= 0 || cfg->n_heads <= 0 || cfg->head_dim <= 0) return nullptr;
   if (cfg->kv_bits != 2 && cfg->kv_bits != 4 && cfg->kv_bits != 16) return nullptr;
   if (cfg->kv_bits != 16 && (cfg->group_size <= 0 || cfg->head_dim % cfg->group_size != 0)) return nullptr;
+  if (cfg->score_mode != 0 && cfg->score_mode != 1) return nullptr;
   auto* st = new xsv_ref_state;
   st->cfg = *cfg;
   if (st->cfg.softmax_scale == 0.0f) st->cfg.softmax_scale = 1.0f / std::sqrt(static_cast<float>(cfg->head_dim));
@@ -355,12 +363,14 @@ xsv_ref_state* xsv_ref_create(const xsv_ref_config* cfg) {
 
 void xsv_ref_destroy(xsv_ref_state* st) { delete st; }
 
+int xsv_ref_num_sets(const xsv_ref_state* st) { return st->cfg.score_mode == 1 ? st->cfg.n_heads : 1; }
 int xsv_ref_cache_len(const xsv_ref_state* st, int layer) { return st->layers[layer].T; }
+// entries PER SET of the last step's scores / keep list
 int xsv_ref_last_scores_len(const xsv_ref_state* st, int layer) {
-  return static_cast<int>(st->layers[layer].last_scores.size());
+  return static_cast<int>(st->layers[layer].last_scores.size()) / xsv_ref_num_sets(st);
 }
 int xsv_ref_last_keep_len(const xsv_ref_state* st, int layer) {
-  return static_cast<int>(st->layers[layer].last_keep.size());
+  return static_cast<int>(st->layers[layer].last_keep.size()) / xsv_ref_num_sets(st);
 }
 
 // The bf16 view of a layer's cache: (code - z) * s rounded to bf16, or the stored rows (bits 16).
@@ -386,8 +396,8 @@ void xsv_ref_cache_view(const xsv_ref_state* st, int layer, uint16_t* k_out, uin
 //   q, k_new, v_new [H][n][d] bf16
 //   rows/n_rows/out: attention is evaluated for these query rows only (rows NULL → all;
 //                    out NULL → attention skipped; the cache never depends on the output)
-//   forced_keep: when non-NULL (n_forced entries, ascending positions in [cache ; frame]) it
-//                replaces the selection — used to adopt a documented near-tie decision.
+//   forced_keep: when non-NULL ([sets][n_forced], each list ascending positions in [cache ; frame])
+//                it replaces the selection — used to adopt a documented near-tie decision.
 // Returns the new cache length, or a negative value on a bad argument.
 int xsv_ref_step(xsv_ref_state* st, int layer, const uint16_t* q, const uint16_t* k_new,
                  const uint16_t* v_new, const int32_t* rows, int n_rows, float* out,
@@ -397,6 +407,7 @@ int xsv_ref_step(xsv_ref_state* st, int layer, const uint16_t* q, const uint16_t
   RefLayer& L = st->layers[layer];
   const int H = c.n_heads, d = c.head_dim, n = c.tokens_per_frame;
   const int Tc = L.T, T = Tc + n;
+  const int sets = xsv_ref_num_sets(st);
 
   // [cache view ; current frame], per head.
   std::vector<uint16_t> k_all(static_cast<size_t>(H) * T * d), v_all(static_cast<size_t>(H) * T * d);
@@ -424,51 +435,72 @@ int xsv_ref_step(xsv_ref_state* st, int layer, const uint16_t* q, const uint16_t
   const int T_first = L.T_first, T_cur = n;
 
   // Sec. 3.2: prune once T exceeds the budget; first and current frames are always kept.
-  std::vector<int32_t> keep;
+  // One index set per layer (score_mode 0) or one per head (score_mode 1).
+  std::vector<std::vector<int32_t>> keep(sets);
   L.last_scores.clear();
   if (forced_keep != nullptr) {
-    keep.assign(forced_keep, forced_keep + n_forced);
+    for (int s = 0; s < sets; ++s)
+      keep[s].assign(forced_keep + static_cast<size_t>(s) * n_forced, forced_keep + static_cast<size_t>(s + 1) * n_forced);
   } else if (c.budget == 0 || T <= c.budget || L.frames == 0) {
-    keep.resize(T);
-    std::iota(keep.begin(), keep.end(), 0);
+    for (int s = 0; s < sets; ++s) {
+      keep[s].resize(T);
+      std::iota(keep[s].begin(), keep[s].end(), 0);
+    }
   } else {
     const int P = T - T_first - T_cur;
     int k = std::max(0, c.budget - T_first - T_cur);
     k = std::min(k, P);
-    std::vector<float> scores(P);
-    if (k > 0 && k < P) {
-      std::vector<uint16_t> k_mid(static_cast<size_t>(H) * P * d);
-      for (int h = 0; h < H; ++h)
-        std::memcpy(&k_mid[static_cast<size_t>(h) * P * d], &k_all[(static_cast<size_t>(h) * T + T_first) * d],
-                    static_cast<size_t>(P) * d * 2);
-      xsv_ref_score(q, k_mid.data(), H, n, c.n_special, P, d, c.pool_size, scores.data());
-      L.last_scores = scores;
+    const bool scored = k > 0 && k < P;
+    for (int s = 0; s < sets; ++s) {
+      std::vector<float> scores(P);
+      if (scored) {
+        if (c.score_mode == 0) {
+          std::vector<uint16_t> k_mid(static_cast<size_t>(H) * P * d);
+          for (int h = 0; h < H; ++h)
+            std::memcpy(&k_mid[static_cast<size_t>(h) * P * d], &k_all[(static_cast<size_t>(h) * T + T_first) * d],
+                        static_cast<size_t>(P) * d * 2);
+          xsv_ref_score(q, k_mid.data(), H, n, c.n_special, P, d, c.pool_size, scores.data());
+        } else {
+          // head s alone: the same score with "all heads" = this one head
+          xsv_ref_score(q + static_cast<size_t>(s) * n * d, &k_all[(static_cast<size_t>(s) * T + T_first) * d], 1, n,
+                        c.n_special, P, d, c.pool_size, scores.data());
+        }
+        L.last_scores.insert(L.last_scores.end(), scores.begin(), scores.end());
+      }
+      keep[s].resize(T_first + k + T_cur);
+      xsv_ref_select(scores.data(), P, k, T_first, T_cur, keep[s].data());
     }
-    keep.resize(T_first + k + T_cur);
-    xsv_ref_select(scores.data(), P, k, T_first, T_cur, keep.data());
   }
-  const int Tn = static_cast<int>(keep.size());
-  for (int i = 0; i < Tn; ++i)
-    if (keep[i] < 0 || keep[i] >= T || (i > 0 && keep[i] <= keep[i - 1])) return -2;
-  L.last_keep = keep;
+  const int Tn = static_cast<int>(keep[0].size());
+  L.last_keep.clear();
+  for (int s = 0; s < sets; ++s) {
+    if (static_cast<int>(keep[s].size()) != Tn) return -2;
+    for (int i = 0; i < Tn; ++i)
+      if (keep[s][i] < 0 || keep[s][i] >= T || (i > 0 && keep[s][i] <= keep[s][i - 1])) return -2;
+    L.last_keep.insert(L.last_keep.end(), keep[s].begin(), keep[s].end());
+  }
 
   // Gather the retained rows (same indices for keys and values) and their token ids.
   std::vector<uint16_t> k_kept(static_cast<size_t>(H) * Tn * d), v_kept(static_cast<size_t>(H) * Tn * d);
-  for (int h = 0; h < H; ++h)
+  for (int h = 0; h < H; ++h) {
+    const std::vector<int32_t>& kp = keep[sets == 1 ? 0 : h];
     for (int i = 0; i < Tn; ++i) {
-      std::memcpy(&k_kept[(static_cast<size_t>(h) * Tn + i) * d], &k_all[(static_cast<size_t>(h) * T + keep[i]) * d], d * 2);
-      std::memcpy(&v_kept[(static_cast<size_t>(h) * Tn + i) * d], &v_all[(static_cast<size_t>(h) * T + keep[i]) * d], d * 2);
-    }
-  std::vector<int32_t> tf(Tn), ti(Tn);
-  for (int i = 0; i < Tn; ++i) {
-    if (keep[i] < Tc) {
-      tf[i] = L.token_frame[keep[i]];
-      ti[i] = L.token_index[keep[i]];
-    } else {
-      tf[i] = frame_id;
-      ti[i] = keep[i] - Tc;
+      std::memcpy(&k_kept[(static_cast<size_t>(h) * Tn + i) * d], &k_all[(static_cast<size_t>(h) * T + kp[i]) * d], d * 2);
+      std::memcpy(&v_kept[(static_cast<size_t>(h) * Tn + i) * d], &v_all[(static_cast<size_t>(h) * T + kp[i]) * d], d * 2);
     }
   }
+  std::vector<int32_t> tf(static_cast<size_t>(sets) * Tn), ti(static_cast<size_t>(sets) * Tn);
+  for (int s = 0; s < sets; ++s)
+    for (int i = 0; i < Tn; ++i) {
+      const int src = keep[s][i];
+      if (src < Tc) {
+        tf[static_cast<size_t>(s) * Tn + i] = L.token_frame[static_cast<size_t>(s) * Tc + src];
+        ti[static_cast<size_t>(s) * Tn + i] = L.token_index[static_cast<size_t>(s) * Tc + src];
+      } else {
+        tf[static_cast<size_t>(s) * Tn + i] = frame_id;
+        ti[static_cast<size_t>(s) * Tn + i] = src - Tc;
+      }
+    }
   L.token_frame.swap(tf);
   L.token_index.swap(ti);
 
