@@ -162,16 +162,10 @@ template <int BITS, int G, int NH>
 __device__ __forceinline__ void store_cache_tile(const Stage<BITS, G, NH>& st, uint16_t* lds, int u) {
   using S = Stage<BITS, G, NH>;
   const int r0 = u / S::kRI, o = u % S::kRI;
-  // (code - zero) * scale as one fused multiply-add per element: code * scale + (-zero * scale).
-  // It differs from the cache's canonical two-step value by at most one fp32 rounding of
-  // zero * scale, far below the bf16 rounding that follows.
-  float nzs[S::kQuant ? S::kSets : 1][S::kPer];
-  if constexpr (S::kQuant) {
-#pragma unroll
-    for (int set = 0; set < S::kSets; ++set)
-#pragma unroll
-      for (int e = 0; e < S::kPer; ++e) nzs[set][e] = -st.pz[set][e] * st.ps[set][e];
-  }
+  // The cache's canonical view: (code - zero) exactly, ONE fp32 multiply by the scale, then bf16.
+  // (A fused code * scale + (-zero * scale) would save an instruction per element, but it rounds
+  // zero * scale first and so breaks ties differently: products of a small integer with
+  // scale = range / levels land on bf16 midpoints often enough to move a dominant key's logit.)
 #pragma unroll
   for (int it = 0; it < S::kIter; ++it) {
     uint16_t* dst = lds + (r0 + it * S::kRowStep) * kLdsStride + o * S::kPer;
@@ -184,8 +178,7 @@ __device__ __forceinline__ void store_cache_tile(const Stage<BITS, G, NH>& st, u
       uint32_t pk[S::kPer / 2];
 #pragma unroll
       for (int e = 0; e < S::kPer; e += 2)
-        pk[e / 2] = pack_bf16(__builtin_fmaf(f[e], st.ps[set][e], nzs[set][e]),
-                              __builtin_fmaf(f[e + 1], st.ps[set][e + 1], nzs[set][e + 1]));
+        pk[e / 2] = pack_bf16((f[e] - st.pz[set][e]) * st.ps[set][e], (f[e + 1] - st.pz[set][e + 1]) * st.ps[set][e + 1]);
 #pragma unroll
       for (int w = 0; w < S::kPer / 8; ++w)
         *reinterpret_cast<uint4*>(dst + w * 8) = make_uint4(pk[4 * w], pk[4 * w + 1], pk[4 * w + 2], pk[4 * w + 3]);
