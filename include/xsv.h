@@ -50,6 +50,10 @@ typedef struct {
   int32_t kv_bits;          /* 2 | 4 = quantized cache (Sec. 3.3); 16 = bf16 cache, no quantizer */
   int32_t group_size;       /* G: 32 | 64; keys: tokens per group, values: channels per group  */
   int32_t pool_size;        /* g of the pooled query (Sec. 3.2), >= 1                           */
+  int32_t score_mode;       /* 0: the paper's score (Sec. 3.2): queries and keys averaged over the heads,
+                               one retained index set per layer shared by all heads.
+                               1: a variant: no averages over heads, every head scores its own keys with
+                               its own pooled queries and keeps its own top-k (same count for all heads) */
   float softmax_scale;      /* 0 → 1/sqrt(head_dim)                                            */
   int32_t max_frames;       /* only for budget == 0: frames the cache must be able to hold     */
 } xsv_config;
@@ -173,7 +177,8 @@ int xsv_cache_len(xsv_ctx* ctx, int layer, int32_t* T);
  *   k_scale, k_zero   float [H][ceil(T/G)][d]                        (kv_bits 2|4 only)
  *   v_scale, v_zero   float [H][T][d/G]                              (kv_bits 2|4 only)
  *   k_bf16, v_bf16    uint16 [H][T][d]: the dequantized view (kv_bits 2|4) or the stored rows (16)
- *   token_frame, token_index int32 [T]: which frame / row each cached token came from. */
+ *   token_frame, token_index int32 [T]: which frame / row each cached token came from
+ *                     (score_mode 1: [H][T], every head has its own retained set). */
 int xsv_cache_export(xsv_ctx* ctx, int layer, uint8_t* k_codes, float* k_scale, float* k_zero, uint8_t* v_codes,
                      float* v_scale, float* v_zero, uint16_t* k_bf16, uint16_t* v_bf16, int32_t* token_frame,
                      int32_t* token_index);
@@ -188,7 +193,8 @@ int xsv_cache_import(xsv_ctx* ctx, int layer, int32_t T, int32_t frames_seen, co
 
 /* What the last xsv_score_prune of this layer decided: n_scores = P if scores were computed (else
  * 0), n_keep = length of the keep list (positions in [cache ; frame]).  Buffers may be NULL to query
- * sizes only; otherwise they must hold n_scores floats / n_keep ints. */
+ * sizes only; otherwise they must hold n_scores floats / n_keep ints (score_mode 1: H lists of that
+ * length each, [H][n_scores] and [H][n_keep]). */
 int xsv_last_selection(xsv_ctx* ctx, int layer, int32_t* n_scores, float* scores, int32_t* n_keep, int32_t* keep);
 
 /* ---- stateless kernels (DEVICE pointers; synchronous: they allocate temporaries and wait) ------- */

@@ -65,18 +65,19 @@ __global__ __launch_bounds__(256) void requant_kernel(const RequantArgs a) {
   const int sb = a.b.src_buf(lb);
   const LayerCache src = layer_cache(a.pool, sb, layer);
   const LayerCache dst = layer_cache(a.pool, sb ^ 1, layer);
-  const int32_t* keep = a.ws.keep + (size_t)layer * a.ws.scores_stride;
+  const int32_t* keep = a.ws.keep + list_index(a.ws.sets, layer, h) * a.ws.scores_stride;
   const int nv = min(kTile, Tn - u * kTile);  // valid new positions in this block
 
   const int s_row = r < nv ? keep[u * kTile + r] : -1;
   const bool row_valid = s_row >= 0;
   const bool from_cache = row_valid && s_row < Tc;
 
-  // token ids travel with the rows (one copy per layer: head 0 writes them)
-  if (h == 0 && cq == 0 && row_valid) {
+  // token ids travel with the rows (one copy per index set: head 0 writes the shared one)
+  if ((h == 0 || a.ws.sets > 1) && cq == 0 && row_valid) {
+    const size_t row0 = a.ws.sets > 1 ? (size_t)h * Tcap : 0;
     const int pos = u * kTile + r;
-    dst.tok_frame[pos] = from_cache ? src.tok_frame[s_row] : a.frame_id;
-    dst.tok_index[pos] = from_cache ? src.tok_index[s_row] : s_row - Tc;
+    dst.tok_frame[row0 + pos] = from_cache ? src.tok_frame[row0 + s_row] : a.frame_id;
+    dst.tok_index[row0 + pos] = from_cache ? src.tok_index[row0 + s_row] : s_row - Tc;
   }
 
   // values: all loads are issued here, ahead of the key phase, so that the kernel pays one memory

@@ -9,6 +9,8 @@
 //   score_kernel        one pass over the packed keys of the prunable middle: dequantized view,
 //                       head mean, dot product with qtilde.  64 tokens x all heads per workgroup,
 //                       16 channels per thread, all loads of a workgroup issued before any use.
+//   Per-head variant (ScoreArgs::per_head, not the paper's): the averages over heads are left out,
+//   qtilde_h comes from head h's partial alone and head h's keys give head h's own score vector.
 //   select_kernel       exact top-k by radix select on order-preserving integer keys held in
 //                       registers (4 passes of 8 bits, histograms in LDS, bin search by a shuffle
 //                       scan), ties at the threshold resolved toward smaller positions, then an
@@ -35,7 +37,7 @@ __global__ __launch_bounds__(kPoolThreads) void pool_query_kernel(const ScoreArg
   const int tid = threadIdx.x, rl = tid >> 3, o = tid & 7;
   const uint16_t* qh = a.b.q[lb] + (size_t)h * a.b.q_sh;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  const float base = (float)(H * n_pooled);
+  const float base = a.per_head ? (float)n_pooled : (float)(H * n_pooled);
 #pragma unroll 4
   for (int r = rl; r < n; r += kPoolThreads / 8) {
     float w;
@@ -82,13 +84,13 @@ hipError_t launch_pool_query(const ScoreArgs& a, hipStream_t stream) {
 // Everything a workgroup needs is requested up front (one memory round trip): the H partial query
 // sums, the group parameters of all heads (staged in LDS, they are shared by the block's tokens)
 // and the thread's packed codes of all heads.
-template <int BITS, int G, int HMAX>
+template <int BITS, int G, int HMAX, bool PER_HEAD>
 __global__ __launch_bounds__(256) void score_kernel(const ScoreArgs a) {
   constexpr bool kQuant = BITS != 16;
   constexpr int kGroups = kQuant ? kTile / G : 1;  // key groups inside a block of 64 positions
   constexpr int kRowDw = kD * BITS / 32;           // dwords per key row
   constexpr int kDwT = kRowDw / 4;                 // dwords per thread (16 channels)
-  __shared__ float qtilde[kD];
+  __shared__ float qtilde[PER_HEAD ? HMAX * kD : kD];  // per head: one row per head of the chunk
   __shared__ float prm[kQuant ? HMAX * kGroups * 2 * kD : 1];  // [head][group][scale|zero][channel]
 
   const int lb = blockIdx.y;
@@ -109,8 +111,8 @@ __global__ __launch_bounds__(256) void score_kernel(const ScoreArgs a) {
     src = reinterpret_cast<const uint32_t*>(lc.kc) + (size_t)pos * kRowDw + cq * kDwT;
     head_stride = (size_t)a.pool.Tcap * kRowDw;
   }
-  if (tid < kD) {  // the H partial sums, in head order
-    const float* part = a.ws.qpart + (size_t)(a.b.layer0 + lb) * a.ws.qpart_rows * kD;
+  const float* part = a.ws.qpart + (size_t)(a.b.layer0 + lb) * a.ws.qpart_rows * kD;
+  if (!PER_HEAD && tid < kD) {  // the H partial sums, in head order
     float s = 0.f;
 #pragma unroll 16
     for (int h = 0; h < H; ++h) s += part[(size_t)h * kD + tid];
@@ -128,10 +130,14 @@ __global__ __launch_bounds__(256) void score_kernel(const ScoreArgs a) {
     for (int h = 0; h < HMAX; ++h)
 #pragma unroll
       for (int i = 0; i < kDwT; ++i) w[h][i] = (valid && h < hn) ? src[(h0 + h) * head_stride + i] : 0u;
+    if constexpr (PER_HEAD) {
+      if (h0 > 0) __syncthreads();  // the previous chunk's rows are no longer read
+      for (int i = tid; i < hn * kD; i += 256) qtilde[i] = part[(size_t)h0 * kD + i];
+    }
     if constexpr (kQuant) {
       const LayerCache lc = layer_cache(a.pool, a.b.src_buf(lb), a.b.layer0 + lb);
       const int gcap = a.pool.Tcap / G;
-      if (h0 > 0) __syncthreads();  // the previous chunk's parameters are no longer read
+      if (h0 > 0 && !PER_HEAD) __syncthreads();  // the previous chunk's parameters are no longer read
       for (int i = tid; i < hn * kGroups * 2 * kD; i += 256) {
         const int c = i % kD, sz = (i / kD) & 1, gi = (i / (2 * kD)) % kGroups, h = i / (2 * kD * kGroups);
         const float* p = sz ? lc.kz : lc.ks;
@@ -142,6 +148,7 @@ __global__ __launch_bounds__(256) void score_kernel(const ScoreArgs a) {
 #pragma unroll
     for (int h = 0; h < HMAX; ++h) {
       if (h < hn) {
+        float x[16];  // head h's key row (this thread's 16 channels), dequantized view
         if constexpr (kQuant) {
           constexpr uint32_t mask = (1u << (BITS & 15)) - 1u;
           const float* ks = prm + ((h * kGroups + (r / G) % kGroups) * 2) * kD + cq * 16;
@@ -149,18 +156,32 @@ __global__ __launch_bounds__(256) void score_kernel(const ScoreArgs a) {
 #pragma unroll
           for (int e = 0; e < 16; ++e) {
             const uint32_t code = (w[h][(e * BITS) / 32] >> ((e * BITS) % 32)) & mask;
-            acc[e] += round_bf16(((float)code - kz[e]) * ks[e]);
+            x[e] = round_bf16(((float)code - kz[e]) * ks[e]);
           }
         } else {
 #pragma unroll
           for (int e = 0; e < 8; ++e) {
-            acc[2 * e] += bf16_lo(w[h][e]);
-            acc[2 * e + 1] += bf16_hi(w[h][e]);
+            x[2 * e] = bf16_lo(w[h][e]);
+            x[2 * e + 1] = bf16_hi(w[h][e]);
           }
+        }
+        if constexpr (PER_HEAD) {
+          const float* qt = qtilde + h * kD + cq * 16;
+          float dot = 0.f;
+#pragma unroll
+          for (int e = 0; e < 16; ++e) dot += qt[e] * x[e];
+          dot += __shfl_xor(dot, 1);
+          dot += __shfl_xor(dot, 2);
+          if (valid && cq == 0)
+            a.ws.scores[list_index(a.ws.sets, a.b.layer0 + lb, h0 + h) * a.ws.scores_stride + (pos - a.T_first)] = dot;
+        } else {
+#pragma unroll
+          for (int e = 0; e < 16; ++e) acc[e] += x[e];
         }
       }
     }
   }
+  if constexpr (PER_HEAD) return;
   const float* qt = qtilde + cq * 16;
   float dot = 0.f;
   const float fH = (float)H;
@@ -168,21 +189,26 @@ __global__ __launch_bounds__(256) void score_kernel(const ScoreArgs a) {
   for (int e = 0; e < 16; ++e) dot += qt[e] * (acc[e] / fH);
   dot += __shfl_xor(dot, 1);
   dot += __shfl_xor(dot, 2);
-  if (valid && cq == 0) a.ws.scores[(size_t)(a.b.layer0 + lb) * a.ws.scores_stride + (pos - a.T_first)] = dot;
+  if (valid && cq == 0) a.ws.scores[list_index(a.ws.sets, a.b.layer0 + lb, 0) * a.ws.scores_stride + (pos - a.T_first)] = dot;
 }
 
-hipError_t launch_score(const ScoreArgs& a, hipStream_t stream) {
+template <bool PER_HEAD>
+static hipError_t launch_score_t(const ScoreArgs& a, hipStream_t stream) {
   const int first_block = a.T_first / kTile;
   const int last_block = (a.T_first + a.P - 1) / kTile;
   const dim3 grid(last_block - first_block + 1, a.b.n_layers);
   const int bits = a.k_plain ? 16 : a.pool.bits, G = a.pool.G;
-  if (bits == 16) hipLaunchKernelGGL((score_kernel<16, 64, 16>), grid, dim3(256), 0, stream, a);
-  else if (bits == 4 && G == 64) hipLaunchKernelGGL((score_kernel<4, 64, 16>), grid, dim3(256), 0, stream, a);
-  else if (bits == 4 && G == 32) hipLaunchKernelGGL((score_kernel<4, 32, 16>), grid, dim3(256), 0, stream, a);
-  else if (bits == 2 && G == 64) hipLaunchKernelGGL((score_kernel<2, 64, 16>), grid, dim3(256), 0, stream, a);
-  else if (bits == 2 && G == 32) hipLaunchKernelGGL((score_kernel<2, 32, 16>), grid, dim3(256), 0, stream, a);
+  if (bits == 16) hipLaunchKernelGGL((score_kernel<16, 64, 16, PER_HEAD>), grid, dim3(256), 0, stream, a);
+  else if (bits == 4 && G == 64) hipLaunchKernelGGL((score_kernel<4, 64, 16, PER_HEAD>), grid, dim3(256), 0, stream, a);
+  else if (bits == 4 && G == 32) hipLaunchKernelGGL((score_kernel<4, 32, 16, PER_HEAD>), grid, dim3(256), 0, stream, a);
+  else if (bits == 2 && G == 64) hipLaunchKernelGGL((score_kernel<2, 64, 16, PER_HEAD>), grid, dim3(256), 0, stream, a);
+  else if (bits == 2 && G == 32) hipLaunchKernelGGL((score_kernel<2, 32, 16, PER_HEAD>), grid, dim3(256), 0, stream, a);
   else return hipErrorInvalidValue;
   return hipGetLastError();
+}
+
+hipError_t launch_score(const ScoreArgs& a, hipStream_t stream) {
+  return a.per_head ? launch_score_t<true>(a, stream) : launch_score_t<false>(a, stream);
 }
 
 // ---- selection --------------------------------------------------------------------------------------
@@ -219,7 +245,7 @@ __device__ __forceinline__ void block_exclusive_scan2(int& a, int& b, int* sh /*
   __syncthreads();
 }
 
-// one workgroup per layer; KPT > 0: each thread keeps its (at most KPT) keys in registers
+// one workgroup per list (layer, or layer and head); KPT > 0: each thread keeps its (at most KPT) keys in registers
 template <int KPT>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectArgs a) {
   __shared__ int hist[256];
@@ -315,9 +341,9 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectArgs a)
 
 hipError_t launch_select(const SelectArgs& a, hipStream_t stream) {
   static_assert(kSelThreads == 256, "one histogram bin per thread");
-  if (a.P <= 16 * kSelThreads) hipLaunchKernelGGL(select_kernel<16>, dim3(a.n_layers), dim3(kSelThreads), 0, stream, a);
-  else if (a.P <= 32 * kSelThreads) hipLaunchKernelGGL(select_kernel<32>, dim3(a.n_layers), dim3(kSelThreads), 0, stream, a);
-  else hipLaunchKernelGGL(select_kernel<0>, dim3(a.n_layers), dim3(kSelThreads), 0, stream, a);
+  if (a.P <= 16 * kSelThreads) hipLaunchKernelGGL(select_kernel<16>, dim3(a.n_lists), dim3(kSelThreads), 0, stream, a);
+  else if (a.P <= 32 * kSelThreads) hipLaunchKernelGGL(select_kernel<32>, dim3(a.n_lists), dim3(kSelThreads), 0, stream, a);
+  else hipLaunchKernelGGL(select_kernel<0>, dim3(a.n_lists), dim3(kSelThreads), 0, stream, a);
   return hipGetLastError();
 }
 
@@ -331,11 +357,11 @@ __global__ __launch_bounds__(256) void fill_keep_kernel(int32_t* keep, int keep_
   out[i] = (keep_middle || i < T_first) ? i : i + P;
 }
 
-hipError_t launch_fill_keep(int32_t* keep, int keep_stride, int n_layers, int T_first, int P, int T_cur, bool keep_middle,
+hipError_t launch_fill_keep(int32_t* keep, int keep_stride, int n_lists, int T_first, int P, int T_cur, bool keep_middle,
                             hipStream_t stream) {
   const int total = T_first + (keep_middle ? P : 0) + T_cur;
   if (total <= 0) return hipSuccess;
-  hipLaunchKernelGGL(fill_keep_kernel, dim3((total + 255) / 256, n_layers), dim3(256), 0, stream, keep, keep_stride,
+  hipLaunchKernelGGL(fill_keep_kernel, dim3((total + 255) / 256, n_lists), dim3(256), 0, stream, keep, keep_stride,
                      T_first, P, T_cur, keep_middle ? 1 : 0);
   return hipGetLastError();
 }

@@ -254,12 +254,14 @@ int do_attend(xsv_ctx* ctx, int layer0, int n_layers, const xsv_tensor* q, const
 
 int do_score_prune(xsv_ctx* ctx, int layer0, int n_layers, const xsv_tensor* q) {
   const PrunePlan p = plan_for(ctx->cfg, ctx->layers[layer0]);
-  int32_t* keep = ctx->ws.keep + (size_t)layer0 * ctx->ws.scores_stride;
+  // the lists of layers [layer0, layer0 + n_layers) are contiguous: sets per layer
+  const int sets = ctx->ws.sets, n_lists = n_layers * sets;
+  int32_t* keep = ctx->ws.keep + list_index(sets, layer0, 0) * ctx->ws.scores_stride;
   if (!p.prune) {
-    if (launch_fill_keep(keep, ctx->ws.scores_stride, n_layers, p.T, 0, 0, true, ctx->work) != hipSuccess) return hip_fail(ctx);
+    if (launch_fill_keep(keep, ctx->ws.scores_stride, n_lists, p.T, 0, 0, true, ctx->work) != hipSuccess) return hip_fail(ctx);
   } else if (!p.score) {
     // k == 0: first ∪ current;  k == P: everything (cannot happen once T > budget, kept for completeness)
-    if (launch_fill_keep(keep, ctx->ws.scores_stride, n_layers, p.T_first, p.P, p.T_cur, p.k == p.P, ctx->work) != hipSuccess)
+    if (launch_fill_keep(keep, ctx->ws.scores_stride, n_lists, p.T_first, p.P, p.T_cur, p.k == p.P, ctx->work) != hipSuccess)
       return hip_fail(ctx);
   } else {
     ScoreArgs s{};
@@ -274,13 +276,14 @@ int do_score_prune(xsv_ctx* ctx, int layer0, int n_layers, const xsv_tensor* q) 
     s.T_first = p.T_first;
     s.P = p.P;
     s.k_plain = nullptr;
+    s.per_head = ctx->cfg.score_mode == 1;
     if (launch_pool_query(s, ctx->work) != hipSuccess) return hip_fail(ctx);
     if (launch_score(s, ctx->work) != hipSuccess) return hip_fail(ctx);
     SelectArgs sel{};
-    sel.scores = ctx->ws.scores + (size_t)layer0 * ctx->ws.scores_stride;
+    sel.scores = ctx->ws.scores + list_index(sets, layer0, 0) * ctx->ws.scores_stride;
     sel.keep = keep;
     sel.scores_stride = sel.keep_stride = ctx->ws.scores_stride;
-    sel.n_layers = n_layers;
+    sel.n_lists = n_lists;
     sel.P = p.P; sel.k = p.k; sel.T_first = p.T_first; sel.T_cur = p.T_cur;
     if (launch_select(sel, ctx->work) != hipSuccess) return hip_fail(ctx);
   }
@@ -366,6 +369,7 @@ int xsv_create(const xsv_config* cfg, void* hip_stream, xsv_ctx** out) {
       c.budget < 0 || c.pool_size < 1 || !(c.softmax_scale >= 0.0f) || !std::isfinite(c.softmax_scale))
     return XSV_ERR_ARG;
   if (c.kv_bits != 2 && c.kv_bits != 4 && c.kv_bits != 16) return XSV_ERR_ARG;
+  if (c.score_mode != 0 && c.score_mode != 1) return XSV_ERR_ARG;
   if (c.head_dim != kD) return XSV_ERR_UNSUPPORTED;
   if (c.kv_bits == 16) c.group_size = 64;
   if (c.group_size != 32 && c.group_size != 64) return c.group_size > 0 ? XSV_ERR_UNSUPPORTED : XSV_ERR_ARG;
@@ -413,6 +417,7 @@ int xsv_create(const xsv_config* cfg, void* hip_stream, xsv_ctx** out) {
   std::memset(&p, 0, sizeof(p));
   p.L = c.n_layers; p.H = c.n_heads; p.bits = c.kv_bits; p.G = c.group_size;
   p.Tcap = round_up((int)cap_tokens, kTile);
+  p.sets = c.score_mode == 1 ? c.n_heads : 1;
   const size_t slabs = 2 * (size_t)c.n_layers;
   int rc = XSV_OK;
   auto A = [&](auto** ptr, size_t count, bool zero) { if (rc == XSV_OK) rc = dev_alloc(ctx, ptr, count, zero); };
@@ -432,8 +437,9 @@ int xsv_create(const xsv_config* cfg, void* hip_stream, xsv_ctx** out) {
   std::memset(&w, 0, sizeof(w));
   w.scores_stride = p.Tcap + (int)n;
   w.qpart_rows = c.n_heads;
-  A(&w.scores, (size_t)c.n_layers * w.scores_stride, true);
-  A(&w.keep, (size_t)c.n_layers * w.scores_stride, true);
+  w.sets = p.sets;
+  A(&w.scores, (size_t)c.n_layers * w.sets * w.scores_stride, true);
+  A(&w.keep, (size_t)c.n_layers * w.sets * w.scores_stride, true);
   A(&w.qpart, (size_t)c.n_layers * w.qpart_rows * kD, true);
   // partial attention outputs: up to 16 key ranges for one layer, or 2 per layer when batched
   // (partials are stored in blocks of 32 query rows per head)
@@ -735,8 +741,10 @@ int xsv_cache_export(xsv_ctx* ctx, int layer, uint8_t* k_codes, float* k_scale, 
   back(v_scale, u.v_scale, n_vp * 4); back(v_zero, u.v_zero, n_vp * 4);
   back(k_bf16, u.k_bf16, n_el * 2); back(v_bf16, u.v_bf16, n_el * 2);
   const LayerCache lc = layer_cache(ctx->pool, L.buf, layer);
-  back(token_frame, lc.tok_frame, (size_t)T * 4);
-  back(token_index, lc.tok_index, (size_t)T * 4);
+  for (int st = 0; st < ctx->pool.sets; ++st) {  // device rows are Tcap apart, host rows T
+    back(token_frame ? token_frame + (size_t)st * T : nullptr, lc.tok_frame + (size_t)st * ctx->pool.Tcap, (size_t)T * 4);
+    back(token_index ? token_index + (size_t)st * T : nullptr, lc.tok_index + (size_t)st * ctx->pool.Tcap, (size_t)T * 4);
+  }
   if (!good || hipStreamSynchronize(ctx->stream) != hipSuccess) return hip_fail(ctx);
   return XSV_OK;
 }
@@ -801,9 +809,9 @@ int xsv_cache_import(xsv_ctx* ctx, int layer, int32_t T, int32_t frames_seen, co
            hipMemcpy(lc.vs, vs.data(), vs.size() * 4, hipMemcpyHostToDevice) == hipSuccess &&
            hipMemcpy(lc.vz, vz.data(), vz.size() * 4, hipMemcpyHostToDevice) == hipSuccess;
   }
-  if (T > 0)
-    good = good && hipMemcpy(lc.tok_frame, token_frame, (size_t)T * 4, hipMemcpyHostToDevice) == hipSuccess &&
-           hipMemcpy(lc.tok_index, token_index, (size_t)T * 4, hipMemcpyHostToDevice) == hipSuccess;
+  for (int st = 0; T > 0 && st < p.sets; ++st)
+    good = good && hipMemcpy(lc.tok_frame + (size_t)st * p.Tcap, token_frame + (size_t)st * T, (size_t)T * 4, hipMemcpyHostToDevice) == hipSuccess &&
+           hipMemcpy(lc.tok_index + (size_t)st * p.Tcap, token_index + (size_t)st * T, (size_t)T * 4, hipMemcpyHostToDevice) == hipSuccess;
   if (!good) return hip_fail(ctx);
   L.T = T;
   L.frames = frames_seen;
@@ -820,12 +828,16 @@ int xsv_last_selection(xsv_ctx* ctx, int layer, int32_t* n_scores, float* scores
   if (n_scores) *n_scores = L.last_P;
   if (n_keep) *n_keep = L.last_keep;
   bool good = true;
-  if (scores && L.last_P > 0)
-    good = hipMemcpyAsync(scores, ctx->ws.scores + (size_t)layer * ctx->ws.scores_stride, (size_t)L.last_P * 4,
-                          hipMemcpyDeviceToHost, ctx->stream) == hipSuccess;
-  if (keep && L.last_keep > 0 && good)
-    good = hipMemcpyAsync(keep, ctx->ws.keep + (size_t)layer * ctx->ws.scores_stride, (size_t)L.last_keep * 4,
-                          hipMemcpyDeviceToHost, ctx->stream) == hipSuccess;
+  const int sets = ctx->ws.sets;
+  for (int st = 0; st < sets && good; ++st) {  // device lists are scores_stride apart, host lists packed
+    const size_t row = (list_index(sets, layer, 0) + st) * ctx->ws.scores_stride;
+    if (scores && L.last_P > 0)
+      good = hipMemcpyAsync(scores + (size_t)st * L.last_P, ctx->ws.scores + row, (size_t)L.last_P * 4, hipMemcpyDeviceToHost,
+                            ctx->stream) == hipSuccess;
+    if (keep && L.last_keep > 0 && good)
+      good = hipMemcpyAsync(keep + (size_t)st * L.last_keep, ctx->ws.keep + row, (size_t)L.last_keep * 4, hipMemcpyDeviceToHost,
+                            ctx->stream) == hipSuccess;
+  }
   if (!good || hipStreamSynchronize(ctx->stream) != hipSuccess) return hip_fail(ctx);
   return XSV_OK;
 }
@@ -882,6 +894,7 @@ int xsv_score(void* hip_stream, xsv_tensor q, const void* k_mid_bf16, int H, int
   s.b.q[0] = static_cast<const uint16_t*>(q.ptr);
   s.b.q_sh = q.stride_head; s.b.q_st = q.stride_token;
   s.ws.qpart_rows = H;
+  s.ws.sets = 1;
   s.ws.qpart = tmp.get<float>((size_t)s.ws.qpart_rows * kD);
   if (!s.ws.qpart) return XSV_ERR_OOM;
   s.ws.scores = scores;
@@ -900,7 +913,7 @@ int xsv_topk_keep(void* hip_stream, const float* scores, int P, int k, int T_fir
     e = launch_fill_keep(keep, 0, 1, T_first, P, T_cur, k == P, stream);
   } else {
     SelectArgs s{};
-    s.scores = scores; s.keep = keep; s.n_layers = 1; s.P = P; s.k = k; s.T_first = T_first; s.T_cur = T_cur;
+    s.scores = scores; s.keep = keep; s.n_lists = 1; s.P = P; s.k = k; s.T_first = T_first; s.T_cur = T_cur;
     e = launch_select(s, stream);
   }
   if (e != hipSuccess) return XSV_ERR_HIP;

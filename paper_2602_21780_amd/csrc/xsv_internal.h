@@ -8,7 +8,8 @@
 //                                       of one channel are one dword, the unit the PV MFMA consumes
 //           vs, vz [Tcap][64/G] fp32    scale / zero point per (token, group of G channels)
 //   bits == 16: kc rows are 64 bf16, vc rows are 64 bf16 (still transposed in 64-token blocks).
-//   token ids   tok_frame, tok_index [Tcap] (per layer, shared by the heads)
+//   token ids   tok_frame, tok_index [sets][Tcap] per layer; sets = 1 (one retained index set per layer, shared by
+//               the heads) or H (one per head, see xsv_config.score_mode)
 // Every layer has two such buffers; a step reads one and writes the other.
 #pragma once
 
@@ -31,15 +32,21 @@ struct CachePool {
   int32_t* tok_frame;
   int32_t* tok_index;
   int L, H, Tcap, bits, G;
+  int sets;  // retained index sets per layer: 1, or H when every head selects for itself
 
   // slab = one (buffer, layer); sizes in elements of the respective array
   __host__ __device__ size_t code_row_bytes() const { return (size_t)kD * bits / 8; }
   __host__ __device__ size_t code_slab() const { return (size_t)H * Tcap * code_row_bytes(); }
   __host__ __device__ size_t kparam_slab() const { return (size_t)H * (Tcap / G) * kD; }
   __host__ __device__ size_t vparam_slab() const { return (size_t)H * Tcap * (kD / G); }
-  __host__ __device__ size_t tok_slab() const { return (size_t)Tcap; }
+  __host__ __device__ size_t tok_slab() const { return (size_t)(sets > 1 ? sets : 1) * Tcap; }
   __host__ __device__ size_t slab_index(int buf, int layer) const { return (size_t)buf * L + layer; }
 };
+
+// index of the score vector / keep list / token-id row that head h of `layer` uses
+__host__ __device__ inline size_t list_index(int sets, int layer, int h) {
+  return sets > 1 ? (size_t)layer * sets + h : (size_t)layer;
+}
 
 // One layer's view of the pool (device pointers of one buffer), head 0.
 struct LayerCache {
@@ -83,14 +90,15 @@ struct Batch {
 
 // Per-layer workspaces (device), indexed by pool layer.
 struct Workspace {
-  float* scores;      // [L][Tcap + n]      importance of the middle tokens
-  int32_t* keep;      // [L][Tcap + n]      keep list
+  float* scores;      // [L][sets][Tcap + n]  importance of the middle tokens
+  int32_t* keep;      // [L][sets][Tcap + n]  keep list
   float* qpart;       // [L][qpart_rows][64] partial weighted query sums
   uint16_t* attn_o;   // [pieces][batch layers][H][ceil(n/32)] blocks of 32 rows x 64 fp16 mantissas of the unnormalized
                       // partial outputs, each block stored [16-byte piece 0..3][lane half][row] (4 KB)
   float* attn_ml;     // [pieces][batch layers][H][n][4]  softmax reference (log2 domain), row sum, row scale, -
   int scores_stride;  // Tcap + n
   int qpart_rows;
+  int sets;           // lists per layer (CachePool::sets)
 };
 
 // ---- launchers (defined in the .hip files; every one only enqueues on `stream`) -----------------
@@ -128,20 +136,21 @@ struct ScoreArgs {
   int T_first, P;  // middle = cache positions [T_first, T_first + P)
   // stateless form: keys come from a plain bf16 tensor [H][P][64] instead of the pool
   const uint16_t* k_plain;
+  int per_head;  // 1: no averages over heads, head h's scores go to list (layer, h)
 };
 hipError_t launch_pool_query(const ScoreArgs& a, hipStream_t stream);
 hipError_t launch_score(const ScoreArgs& a, hipStream_t stream);
 
 struct SelectArgs {
-  const float* scores;  // [n_layers][scores_stride]
-  int32_t* keep;        // [n_layers][keep_stride]
+  const float* scores;  // [n_lists][scores_stride]
+  int32_t* keep;        // [n_lists][keep_stride]
   int scores_stride, keep_stride;
-  int n_layers;
+  int n_lists;          // layers x index sets per layer
   int P, k, T_first, T_cur;
 };
 hipError_t launch_select(const SelectArgs& a, hipStream_t stream);
 // keep = 0..T-1 (nothing pruned) or first ∪ current (k == 0)
-hipError_t launch_fill_keep(int32_t* keep, int keep_stride, int n_layers, int T_first, int P, int T_cur,
+hipError_t launch_fill_keep(int32_t* keep, int keep_stride, int n_lists, int T_first, int P, int T_cur,
                             bool keep_middle, hipStream_t stream);
 
 struct RequantArgs {

@@ -30,7 +30,7 @@ class xsv_config(C.Structure):
     _fields_ = [
         ("n_layers", C.c_int32), ("n_heads", C.c_int32), ("head_dim", C.c_int32),
         ("tokens_per_frame", C.c_int32), ("n_special", C.c_int32), ("budget", C.c_int32),
-        ("kv_bits", C.c_int32), ("group_size", C.c_int32), ("pool_size", C.c_int32),
+        ("kv_bits", C.c_int32), ("group_size", C.c_int32), ("pool_size", C.c_int32), ("score_mode", C.c_int32),
         ("softmax_scale", C.c_float), ("max_frames", C.c_int32),
     ]
 
@@ -140,9 +140,9 @@ class Context:
     """Owner of an xsv_ctx.  Method names follow the C entry points."""
 
     def __init__(self, n_layers, n_heads, head_dim, tokens_per_frame, n_special, budget, kv_bits, group_size,
-                 pool_size=16, softmax_scale=0.0, max_frames=0, stream=None):
+                 pool_size=16, softmax_scale=0.0, max_frames=0, stream=None, score_mode=0):
         self.cfg = xsv_config(n_layers, n_heads, head_dim, tokens_per_frame, n_special, budget, kv_bits, group_size,
-                              pool_size, softmax_scale, max_frames)
+                              pool_size, score_mode, softmax_scale, max_frames)
         self._stream = stream
         self._h = C.c_void_p()
         _check(lib().xsv_create(C.byref(self.cfg), _stream_ptr(stream), C.byref(self._h)), "xsv_create")
@@ -266,8 +266,9 @@ class Context:
         vz = np.zeros((H, T, d // G), np.float32) if quant else None
         kb = np.zeros((H, T, d), np.uint16)
         vb = np.zeros((H, T, d), np.uint16)
-        tf = np.zeros(T, np.int32)
-        ti = np.zeros(T, np.int32)
+        lead = (H,) if self.cfg.score_mode == 1 else ()     # one retained set per head, or one per layer
+        tf = np.zeros(lead + (T,), np.int32)
+        ti = np.zeros(lead + (T,), np.int32)
         _check(lib().xsv_cache_export(self._h, layer, _np_ptr(kc), _np_ptr(ks), _np_ptr(kz), _np_ptr(vc), _np_ptr(vs),
                                       _np_ptr(vz), _np_ptr(kb), _np_ptr(vb), _np_ptr(tf), _np_ptr(ti)), "xsv_cache_export")
         return CacheDump(T, kc, ks, kz, vc, vs, vz, kb, vb, tf, ti)
@@ -286,8 +287,9 @@ class Context:
     def last_selection(self, layer=0):
         ns, nk = C.c_int32(), C.c_int32()
         _check(lib().xsv_last_selection(self._h, layer, C.byref(ns), None, C.byref(nk), None), "xsv_last_selection")
-        scores = np.zeros(ns.value, np.float32)
-        keep = np.zeros(nk.value, np.int32)
+        lead = (self.cfg.n_heads,) if self.cfg.score_mode == 1 else ()
+        scores = np.zeros(lead + (ns.value,), np.float32)
+        keep = np.zeros(lead + (nk.value,), np.int32)
         _check(lib().xsv_last_selection(self._h, layer, C.byref(ns), _np_ptr(scores), C.byref(nk), _np_ptr(keep)),
                "xsv_last_selection")
         return scores, keep

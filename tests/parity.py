@@ -22,23 +22,31 @@ def make_pair(spec, layers=None, **over):
     L = spec.n_layers if layers is None else len(layers)
     st = ref.RefStream(L, spec.n_heads, spec.head_dim, spec.tokens_per_frame, spec.n_special,
                        over.get("budget", spec.budget), over.get("kv_bits", spec.kv_bits),
-                       over.get("group_size", spec.group_size), spec.pool_size)
+                       over.get("group_size", spec.group_size), spec.pool_size, score_mode=over.get("score_mode", 0))
     return ctx, st
 
 
 def oracle_keep_preview(st, layer, q16, n, n_special, pool, budget):
-    """The keep list the oracle is about to choose, from its stateless functions (no state change)."""
+    """The keep list(s) the oracle is about to choose, from its stateless functions (no state change).
+    One index set per layer: (keep [T'], scores [P] or None); one per head: ([H][T'], [H][P] or None)."""
     Tc = st.cache_len(layer)
     T = Tc + n
+    sets = st.sets
+    per_set = (lambda a: a) if sets == 1 else (lambda a: np.stack([a] * sets))
     if budget == 0 or T <= budget or Tc == 0:
-        return np.arange(T, dtype=np.int32), None
+        return per_set(np.arange(T, dtype=np.int32)), None
     P = T - 2 * n
     k = min(max(0, budget - 2 * n), P)
     if not (0 < k < P):
-        return ref.select(np.zeros(P, np.float32), k, n, n), None
+        return per_set(ref.select(np.zeros(P, np.float32), k, n, n)), None
     k_view, _ = st.view(layer)
-    scores, _ = ref.score(q16, np.ascontiguousarray(k_view[:, n:n + P]), n_special, pool)
-    return ref.select(scores, k, n, n), scores
+    if sets == 1:
+        scores, _ = ref.score(q16, np.ascontiguousarray(k_view[:, n:n + P]), n_special, pool)
+        return ref.select(scores, k, n, n), scores
+    # every head on its own: the oracle's score with that head as the only head
+    scores = np.stack([ref.score(np.ascontiguousarray(q16[h:h + 1]), np.ascontiguousarray(k_view[h:h + 1, n:n + P]),
+                                 n_special, pool)[0] for h in range(sets)])
+    return np.stack([ref.select(scores[h], k, n, n) for h in range(sets)]), scores
 
 
 def check_keep(keep_gpu, keep_ref, scores_ref, k, n_first):
@@ -85,10 +93,15 @@ def step_and_compare(ctx, st, spec, layer_gpu, layer_ref, q, k, v, rows=None, bu
         out_gpu = ctx.step(layer_gpu, q, k, v)
     scores_gpu, keep_gpu = ctx.last_selection(layer_gpu)
     keep_ref, scores_ref = oracle_keep_preview(st, layer_ref, q16, n, spec.n_special, spec.pool_size, budget)
-    kk = len(keep_ref) - 2 * n
-    ties = check_keep(keep_gpu, keep_ref, scores_ref, kk, n)
+    kk = keep_ref.shape[-1] - 2 * n
+    if st.sets == 1:
+        ties = check_keep(keep_gpu, keep_ref, scores_ref, kk, n)
+    else:
+        assert keep_gpu.shape == keep_ref.shape
+        ties = sum(check_keep(keep_gpu[h], keep_ref[h], None if scores_ref is None else scores_ref[h], kk, n)
+                   for h in range(st.sets))
     if scores_ref is not None:
-        assert len(scores_gpu) == len(scores_ref)
+        assert scores_gpu.shape == scores_ref.shape
         err = float(np.max(np.abs(scores_gpu - scores_ref)))
         assert err <= TIE_EPS * (1.0 + float(np.abs(scores_ref).max())), f"importance scores differ by {err:.3e}"
     out_ref, T_ref = st.step(layer_ref, q16, k16, v16, rows=rows, forced_keep=keep_gpu if ties else None)

@@ -59,6 +59,43 @@ def test_short_extra_key_range(short):
     run_stream(spec, 10, short=short)
 
 
+def test_dominant_keys_whose_dequantized_values_are_rounding_ties():
+    """A small cache with strong key outliers: single keys dominate the softmax, and (code - zero) * scale lands on
+    bf16 midpoints for some of them, so the output shows whether attention reads exactly the cache's canonical view
+    (a dequantization that rounds differently moves such a key's weight by a few percent)."""
+    spec = CONFIGS[0].with_(name="ties", n_heads=2, tokens_per_frame=150, budget=520, kv_bits=4, group_size=32, n_layers=2, seed=17)
+    run_stream(spec, 7)
+
+
+@pytest.mark.parametrize("bits,G,H", [(4, 32, 2), (4, 64, 5), (2, 64, 3), (16, 64, 2), (4, 64, 20)])
+def test_per_head_selection(bits, G, H):
+    """score_mode 1: every head scores its own keys and keeps its own top-k; lists, token ids, scores and
+    the re-quantized cache against the oracle's per-head mode."""
+    spec = CONFIGS[0].with_(name=f"perhead-b{bits}-g{G}-h{H}", n_heads=H, tokens_per_frame=150, budget=520, kv_bits=bits,
+                            group_size=G, n_layers=2, seed=17)
+    run_stream(spec, 7, score_mode=1)
+
+
+def test_per_head_selection_batched_equals_per_layer_steps():
+    spec = CONFIGS[0].with_(name="perhead-batched", n_layers=3, n_heads=4, tokens_per_frame=150, budget=400, group_size=64, seed=19)
+    ctx_a = xsv.Context.from_spec(spec, score_mode=1)
+    ctx_b = xsv.Context.from_spec(spec, score_mode=1)
+    src = FrameSource(spec, DEV)
+    for f in range(6):
+        q, k, v = src.frame(f)
+        out_a = ctx_a.step_all_layers(q, k, v)
+        out_b = torch.stack([ctx_b.step(l, q[l], k[l], v[l]) for l in range(spec.n_layers)])
+        torch.cuda.synchronize()
+        assert torch.equal(out_a, out_b)
+        for l in range(spec.n_layers):
+            parity.compare_cache(ctx_a.cache_export(l), ctx_b.cache_export(l), True)
+            sa, sb = ctx_a.last_selection(l), ctx_b.last_selection(l)
+            assert sa[1].shape == (4, ctx_a.cache_len(l))
+            assert np.array_equal(sa[0], sb[0]) and np.array_equal(sa[1], sb[1])
+    ctx_a.destroy()
+    ctx_b.destroy()
+
+
 def test_budget_below_two_frames_keeps_first_and_current():
     spec = CONFIGS[0].with_(name="k0", budget=100)
     run_stream(spec, 4)
