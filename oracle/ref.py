@@ -185,9 +185,9 @@ class RefStream:
             raise ValueError("xsv_ref_create rejected the configuration")
 
     def close(self):
-        if self._h:
-            lib().xsv_ref_destroy(self._h)
-            self._h = None
+        if getattr(self, "_h", None) and _lib is not None:     # at interpreter exit the module may already be gone
+            _lib.xsv_ref_destroy(self._h)
+        self._h = None
 
     def __del__(self):
         self.close()

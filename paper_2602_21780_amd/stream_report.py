@@ -6,6 +6,7 @@ per-frame cost stay constant; Sec. 4.4 reports the same comparison on video stre
     python -m paper_2602_21780_amd.stream_report --configs 0,1,2,4
     python -m paper_2602_21780_amd.stream_report --long 200
     python -m paper_2602_21780_amd.stream_report --granularity
+    python -m paper_2602_21780_amd.stream_report --selector-sweep
 
 `--configs`: frames/s of each listed workload at its saturated cache, layer by layer through xsv_step
 (overlap mode 2, one xsv_join per frame), events on the launch stream around each frame's 24 (or 1) steps.
@@ -14,6 +15,11 @@ unbounded bf16 cache (kv_bits 16, budget 0); prints ms/frame and cache bytes at 
 `--granularity`: mean squared error of the two grouping directions of the quantizer (per token: groups of G
 channels; per channel: groups of G tokens) on the synthetic keys (with their outlier channels) and values, at
 4 and 2 bits, G = 64 — the analogue of the paper's Table 1 (Sec. 3.3), through xsv_quantize_k / xsv_quantize_v.
+`--selector-sweep`: one layer of the 24-layer workload's shape on the drifting stream, stepped side by side with an
+unbounded bf16 cache; prints the relative RMS difference of the attention outputs (mean over the frames after
+saturation) for token budgets 2748 (first + current only) .. 8192, pooling sizes 4 / 16 / 64, the per-head
+selector (score_mode 1), pruning without quantization and quantization without pruning — the analogue of the
+paper's cache-length ablation (Sec. 4.5) with output error standing in for the task metrics.
 Inputs are synthetic (seeded), generated on the device outside the timed regions.  One JSON line per row.
 """
 from __future__ import annotations
@@ -86,12 +92,46 @@ def granularity_table(torch, xsv, FrameSource, CONFIGS, G=64):
     return rows
 
 
+def selector_sweep(torch, xsv, FrameSource, CONFIGS, frames=14):
+    """Output difference against the uncompressed cache for variants of budget, pooling size, selector and width."""
+    base = CONFIGS[2].with_(n_layers=1, frames=frames)
+    n = base.tokens_per_frame
+    variants = [("budget 4096, 4-bit, g 16 (the benchmarked setting)", {})]
+    variants += [(f"budget {b}", {"budget": b}) for b in (2 * n, 6144, 8192)]
+    variants += [(f"pooling size {g}", {"pool_size": g}) for g in (4, 64)]
+    variants += [("per-head selection", {"score_mode": 1}),
+                 ("pruning only (bf16 cache)", {"kv_bits": 16}),
+                 ("quantization only (unbounded 4-bit cache)", {"budget": 0}),
+                 ("budget 4096, 2-bit", {"kv_bits": 2})]
+    src = FrameSource(base, "cuda:0", layers=[0])
+    inputs = [src.frame(f) for f in range(frames)]
+    ref_ctx = xsv.Context.from_spec(base, budget=0, kv_bits=16, max_frames=frames + 1)
+    ref_out = [ref_ctx.step(0, q[0], k[0], v[0]).float() for q, k, v in inputs]
+    torch.cuda.synchronize()
+    ref_ctx.destroy()
+    rows = []
+    for label, over in variants:
+        ctx = xsv.Context.from_spec(base, max_frames=frames + 1, **over)
+        errs, T = [], 0
+        for f, (q, k, v) in enumerate(inputs):
+            out = ctx.step(0, q[0], k[0], v[0]).float()
+            if f >= frames - 6:
+                errs.append(float(((out - ref_out[f]) ** 2).mean().sqrt() / (ref_out[f] ** 2).mean().sqrt()))
+            T = ctx.cache_len(0)
+        spec = base.with_(**{k_: v_ for k_, v_ in over.items() if k_ in ("budget", "kv_bits")})
+        rows.append({"variant": label, "cache_tokens": T, "cache_MB_per_layer": round(cache_bytes(spec, T) / 1e6, 2),
+                     "rel_rms_vs_uncompressed": round(sum(errs) / len(errs), 4), "frames_averaged": len(errs)})
+        ctx.destroy()
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--configs", default="", help="comma-separated workload ids of inputs.CONFIGS")
     ap.add_argument("--frames", type=int, default=0, help="frames per workload for --configs (0 = saturation + 12)")
     ap.add_argument("--long", type=int, default=0, help="frames of the long-stream comparison (0 = skip)")
     ap.add_argument("--granularity", action="store_true", help="per-token vs per-channel quantization error table")
+    ap.add_argument("--selector-sweep", action="store_true", help="output error against an uncompressed cache per variant")
     args = ap.parse_args()
 
     import torch
@@ -114,6 +154,10 @@ def main():
 
     if args.granularity:
         for r in granularity_table(torch, xsv, FrameSource, CONFIGS):
+            print(json.dumps(r), flush=True)
+
+    if args.selector_sweep:
+        for r in selector_sweep(torch, xsv, FrameSource, CONFIGS):
             print(json.dumps(r), flush=True)
 
     if args.long:

@@ -259,6 +259,13 @@ def test_24_layer_config_shape_two_layers_sampled_rows():
     run_stream(spec, 6, rows=rows)
 
 
+def test_24_layer_config_shape_per_head_selection_sampled_rows():
+    """cfg 2 shape with every head keeping its own top 1348 of 2722 (score_mode 1), two layers."""
+    spec = CONFIGS[2].with_(n_layers=2)
+    rows = np.array([0, 3, 64, 777, 1311, 1373], np.int32)
+    run_stream(spec, 6, rows=rows, score_mode=1)
+
+
 def test_2bit_config_shape_sampled_rows():
     """cfg 4 shape (1041 tokens, 2-bit, budget 8192) on one layer until the first prune."""
     spec = CONFIGS[4].with_(n_layers=1)
