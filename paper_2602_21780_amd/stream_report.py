@@ -38,11 +38,11 @@ def cache_bytes(spec, T):
     return 2 * T * D * per * spec.n_layers
 
 
-def run_stream(spec, frames, checkpoints, torch, xsv, FrameSource, window=5):
+def run_stream(spec, frames, checkpoints, torch, xsv, FrameSource, window=5, score_mode=0):
     """Steps `frames` frames; returns rows (frame, ms/frame averaged over the `window` frames ending there)."""
     dev = "cuda:0"
     L, n = spec.n_layers, spec.tokens_per_frame
-    ctx = xsv.Context.from_spec(spec, max_frames=frames + 1)
+    ctx = xsv.Context.from_spec(spec, max_frames=frames + 1, score_mode=score_mode)
     ctx.set_overlap(2)
     src = FrameSource(spec, dev)
     out = torch.empty((L, spec.n_heads, n, spec.head_dim), dtype=torch.bfloat16, device=dev)
@@ -129,6 +129,8 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--configs", default="", help="comma-separated workload ids of inputs.CONFIGS")
     ap.add_argument("--frames", type=int, default=0, help="frames per workload for --configs (0 = saturation + 12)")
+    ap.add_argument("--score-mode", type=int, default=0, choices=(0, 1),
+                    help="for --configs: 0 = one retained set per layer (the paper's score), 1 = one per head")
     ap.add_argument("--long", type=int, default=0, help="frames of the long-stream comparison (0 = skip)")
     ap.add_argument("--granularity", action="store_true", help="per-token vs per-channel quantization error table")
     ap.add_argument("--selector-sweep", action="store_true", help="output error against an uncompressed cache per variant")
@@ -146,10 +148,12 @@ def main():
         n = spec.tokens_per_frame
         sat = (spec.budget // n + 2) if spec.budget else 2
         frames = args.frames or min(spec.frames, sat + 12)
-        rows = run_stream(spec, frames, {frames}, torch, xsv, FrameSource, window=max(1, min(10, frames - sat)))
+        rows = run_stream(spec, frames, {frames}, torch, xsv, FrameSource, window=max(1, min(10, frames - sat)),
+                          score_mode=args.score_mode)
         r = rows[-1]
         print(json.dumps({"workload": spec.name, "layers": spec.n_layers, "tokens_per_frame": n, "budget": spec.budget,
-                          "kv_bits": spec.kv_bits, "group_size": spec.group_size, "frames_run": frames,
+                          "kv_bits": spec.kv_bits, "group_size": spec.group_size, "score_mode": args.score_mode,
+                          "frames_run": frames,
                           "frames_per_s": round(1e3 / r["ms_per_frame"], 2), **r}), flush=True)
 
     if args.granularity:

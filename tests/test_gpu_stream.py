@@ -67,6 +67,15 @@ def test_dominant_keys_whose_dequantized_values_are_rounding_ties():
     run_stream(spec, 7)
 
 
+@pytest.mark.parametrize("seed", range(30, 38))
+@pytest.mark.parametrize("bits,G", [(4, 64), (2, 32)])
+def test_small_caches_with_key_outliers_over_seeds(seed, bits, G):
+    """The same kind of stream (few keys, single keys dominating the softmax) over more seeds and code widths."""
+    spec = CONFIGS[0].with_(name=f"peaky-s{seed}", n_heads=2, tokens_per_frame=130, budget=450, kv_bits=bits, group_size=G,
+                            n_layers=1, seed=seed)
+    run_stream(spec, 6)
+
+
 @pytest.mark.parametrize("bits,G,H", [(4, 32, 2), (4, 64, 5), (2, 64, 3), (16, 64, 2), (4, 64, 20)])
 def test_per_head_selection(bits, G, H):
     """score_mode 1: every head scores its own keys and keeps its own top-k; lists, token ids, scores and
