@@ -51,7 +51,8 @@ def main():
     ap.add_argument("--splits", type=int, default=0, help="key ranges per attention launch (0 = auto)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-steps", type=int, default=24, help="layer-steps the CPU-oracle baseline times (about 0.5 s each)")
-    ap.add_argument("--both-forms", action="store_true", help="also time the other launch form (extra kernels in a profile)")
+    ap.add_argument("--one-form", dest="both_forms", action="store_false",
+                    help="skip timing the other launch form (all layers per launch), reported as other_launch_form")
     ap.add_argument("--overlap", type=int, choices=[0, 1, 2], default=2,
                     help="0: prune chain after attention on one stream; 1: on a side stream, joined per call; "
                          "2: side stream, joined lazily (once per frame here)")

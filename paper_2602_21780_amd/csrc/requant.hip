@@ -25,6 +25,8 @@ __device__ __forceinline__ uint16_t bf16_bits(float x) { return __builtin_bit_ca
 
 struct QParam {
   float s, z;
+  float y;    // 1 / s, correctly rounded
+  bool safe;  // the division-free quotient below may be used for this group
 };
 
 __device__ __forceinline__ QParam group_param(float lo, float hi, int bits) {
@@ -34,7 +36,33 @@ __device__ __forceinline__ QParam group_param(float lo, float hi, int bits) {
   QParam p;
   p.s = s;
   p.z = rintf(-lo / s);
+  p.y = 1.0f / s;
+  // magnitudes for which no intermediate of exact_quotient over- or underflows in a way that could
+  // change rint(x / s); anything else (also NaN) takes the division
+  constexpr float kBig = 0x1p60f, kSmall = 0x1p-60f;
+  p.safe = s >= kSmall && s <= kBig && fmaxf(fabsf(lo), fabsf(hi)) <= kBig;
   return p;
+}
+
+// x / s rounded to nearest, bit for bit the IEEE quotient, from y = RN(1 / s) and four fused multiply-adds
+// instead of the eleven-instruction division sequence.  q0 = RN(x y) is within 2 ulp of x / s; the first
+// correction with the remainder r = x - q s makes it faithful (within 1 ulp), and for a faithful q and a
+// correctly rounded reciprocal RN(q + r y) is the correctly rounded quotient (Markstein's theorem; the
+// remainder of a faithful quotient is exact in one FMA).  For |x / s| < 1/2 the low intermediates may lose
+// bits to underflow, which cannot move rint() of the result off zero.
+__device__ __forceinline__ float exact_quotient(float x, float s, float y) {
+  float q = x * y;
+  float r = __builtin_fmaf(-q, s, x);
+  q = __builtin_fmaf(r, y, q);
+  r = __builtin_fmaf(-q, s, x);
+  return __builtin_fmaf(r, y, q);
+}
+
+__device__ __forceinline__ uint32_t quant_code_fast(float x, float s, float y, float z, int bits) {
+  const float hi = (float)((1 << bits) - 1);
+  float q = rintf(exact_quotient(x, s, y)) + z;
+  q = fminf(fmaxf(q, 0.0f), hi);
+  return (uint32_t)q;
 }
 
 __device__ __forceinline__ uint32_t quant_code(float x, float s, float z, int bits) {
@@ -55,7 +83,8 @@ __global__ __launch_bounds__(256) void requant_kernel(const RequantArgs a) {
 
   __shared__ float xk[kTile][kD + 1];
   __shared__ float red_lo[4][kD], red_hi[4][kD];
-  __shared__ float gs[2][kD], gz[2][kD];
+  __shared__ float gs[2][kD], gz[2][kD], gy[2][kD];
+  __shared__ int k_unsafe;  // some key group of this block needs the division
   __shared__ __attribute__((aligned(16))) uint16_t vt[kD][kTile + 8];  // value codes (or bf16), [channel][token]
 
   const int u = blockIdx.x, h = blockIdx.y, lb = blockIdx.z;
@@ -68,6 +97,7 @@ __global__ __launch_bounds__(256) void requant_kernel(const RequantArgs a) {
   const int32_t* keep = a.ws.keep + list_index(a.ws.sets, layer, h) * a.ws.scores_stride;
   const int nv = min(kTile, Tn - u * kTile);  // valid new positions in this block
 
+  if (tid == 0) k_unsafe = 0;  // (ordered before its readers and writers by the barriers of the key phase)
   const int s_row = r < nv ? keep[u * kTile + r] : -1;
   const bool row_valid = s_row >= 0;
   const bool from_cache = row_valid && s_row < Tc;
@@ -169,6 +199,8 @@ __global__ __launch_bounds__(256) void requant_kernel(const RequantArgs a) {
         const QParam q = group_param(lo, hi, BITS);
         gs[gi][c] = q.s;
         gz[gi][c] = q.z;
+        gy[gi][c] = q.y;
+        if (!q.safe) k_unsafe = 1;
         const size_t gidx = ((size_t)h * (Tcap / G) + (size_t)u * kKGroups + gi) * kD + c;
         dst.ks[gidx] = q.s;
         dst.kz[gidx] = q.z;
@@ -180,10 +212,18 @@ __global__ __launch_bounds__(256) void requant_kernel(const RequantArgs a) {
       uint32_t w[kRowDw / 4];
 #pragma unroll
       for (int i = 0; i < kRowDw / 4; ++i) w[i] = 0u;
+      if (!k_unsafe) {
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int c = cq * 16 + e;
-        w[e / kPer] |= quant_code(x[e], gs[gi][c], gz[gi][c], BITS) << ((e % kPer) * BITS);
+        for (int e = 0; e < 16; ++e) {
+          const int c = cq * 16 + e;
+          w[e / kPer] |= quant_code_fast(x[e], gs[gi][c], gy[gi][c], gz[gi][c], BITS) << ((e % kPer) * BITS);
+        }
+      } else {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int c = cq * 16 + e;
+          w[e / kPer] |= quant_code(x[e], gs[gi][c], gz[gi][c], BITS) << ((e % kPer) * BITS);
+        }
       }
       uint32_t* out = reinterpret_cast<uint32_t*>(dst.kc) + ((size_t)h * Tcap + (size_t)u * kTile + r) * kRowDw + cq * (kRowDw / 4);
 #pragma unroll
@@ -234,8 +274,13 @@ __global__ __launch_bounds__(256) void requant_kernel(const RequantArgs a) {
       dst.vs[gidx] = q.s;
       dst.vz[gidx] = q.z;
     }
+    if (__all(q.safe)) {
 #pragma unroll
-    for (int e = 0; e < 16; ++e) vt[cq * 16 + e][r] = row_valid ? (uint16_t)quant_code(x[e], q.s, q.z, BITS) : (uint16_t)0;
+      for (int e = 0; e < 16; ++e) vt[cq * 16 + e][r] = row_valid ? (uint16_t)quant_code_fast(x[e], q.s, q.y, q.z, BITS) : (uint16_t)0;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) vt[cq * 16 + e][r] = row_valid ? (uint16_t)quant_code(x[e], q.s, q.z, BITS) : (uint16_t)0;
+    }
   } else {
 #pragma unroll
     for (int e = 0; e < 16; ++e) vt[cq * 16 + e][r] = row_valid ? bf16_bits(x[e]) : (uint16_t)0;

@@ -77,6 +77,27 @@ def test_quantize_quotients_on_and_next_to_rounding_boundaries(bits):
             assert np.array_equal(codes.cpu().numpy(), rc)
 
 
+@pytest.mark.parametrize("bits", [2, 4])
+def test_quantize_extreme_magnitudes_next_to_ordinary_groups(bits):
+    """Groups of huge (1e30), tiny (1e-30) and ordinary values side by side, per channel and per token: the
+    quantizer's quotient takes its division-free form only where no intermediate can leave the normal range,
+    and both forms must give the oracle's codes."""
+    g = torch.Generator().manual_seed(9)
+    x = torch.randn((2, 192, 64), generator=g)
+    x[0, :, 5] *= 1e30
+    x[0, :, 6] *= 1e-30
+    x[1, 10:20, :] *= 3e25
+    x[1, 100:110, :] *= 1e-28
+    x[1, 64:128, 40] = 2.5e20 + x[1, 64:128, 40] * 1e18
+    xb = x.to(torch.bfloat16).to(DEV)
+    for fn_gpu, fn_ref in ((xsv.quantize_k, ref.quantize_k), (xsv.quantize_v, ref.quantize_v)):
+        for G in (32, 64):
+            codes, scale, zero = fn_gpu(xb, bits, G)
+            rc, rs, rz = fn_ref(to_u16(xb), bits, G)
+            assert np.array_equal(scale.cpu().numpy(), rs) and np.array_equal(zero.cpu().numpy(), rz)
+            assert np.array_equal(codes.cpu().numpy(), rc)
+
+
 @pytest.mark.parametrize("H,n,n_s,P,g", [(2, 64, 5, 192, 16), (16, 1374, 5, 2722, 16), (3, 37, 5, 70, 4), (1, 21, 0, 1, 1)])
 def test_score_matches_oracle(H, n, n_s, P, g):
     print(f"score H={H} n={n} P={P}", flush=True)
