@@ -84,6 +84,13 @@ int xsv_reset(xsv_ctx* ctx);
  * q, k_new, v_new: bf16 [H][n][64] via strides.  out: DEVICE bf16 [H][n][64] contiguous. */
 int xsv_dequant_attend(xsv_ctx* ctx, int layer, xsv_tensor q, xsv_tensor k_new, xsv_tensor v_new, void* out);
 
+/* The frame-wise attention of the alternating-attention backbone (Sec. 3.1: the layers alternate between
+ * attention inside each frame and global attention across frames): out = softmax(scale * q k^T) v over
+ * the frame's own n tokens only, no cache involved and no state touched (any phase, any layer count).
+ * Same kernel as xsv_dequant_attend with an empty cache.  q, k, v: bf16 [H][n][64] via strides;
+ * out: DEVICE bf16 [H][n][64] contiguous. */
+int xsv_frame_attend(xsv_ctx* ctx, xsv_tensor q, xsv_tensor k, xsv_tensor v, void* out);
+
 /* Sec. 3.2 after the append (T = T_cache + n).  If budget == 0, T <= budget, or this is the first
  * frame, everything is kept.  Otherwise, with T_first = T_cur = n, P = T - T_first - T_cur and
  * k = min(max(0, budget - T_first - T_cur), P): the importance of every middle token j is
@@ -163,8 +170,9 @@ int xsv_attend_times(xsv_ctx* ctx, int32_t* launches, float* attend_ms, float* m
 int xsv_chain_times(xsv_ctx* ctx, int32_t* steps, float* score_prune_ms, float* quantize_ms);
 /* Grid (workgroups) of the most recent attention launch of this context, 0 before the first. */
 int xsv_last_attend_workgroups(xsv_ctx* ctx, int32_t* workgroups);
-/* Tuning: workgroup shape of the attention kernel (waves x query rows per wave).  3 (default) = 8 x 64,
- * 0 = 4 x 64, 1 = 4 x 32, 2 = 8 x 32.  Other values: XSV_ERR_ARG.  Results agree to rounding. */
+/* Tuning: workgroup shape of the attention kernel (waves x query rows per wave).  3 = 8 x 64, 0 = 4 x 64,
+ * 1 = 4 x 32, 2 = 8 x 32.  Default: 3, or 2 where blocks of 256 rows pad a frame's tokens less than blocks
+ * of 512 (e.g. 1041 tokens).  Other values: XSV_ERR_ARG.  Results agree to rounding. */
 int xsv_set_attend_variant(xsv_ctx* ctx, int variant);
 
 /* ---- introspection, synchronous, HOST buffers, canonical unpacked layout ------------------------ */

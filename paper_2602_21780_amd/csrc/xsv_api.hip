@@ -49,7 +49,7 @@ struct xsv_ctx {
   std::vector<LayerState> layers;
   std::vector<void*> allocs;
   int splits_single = 0, splits_batched = 0;
-  int attend_variant = 3;  // 8 waves x 64 query rows per workgroup
+  int attend_variant = 3;  // 8 waves x 64 query rows per workgroup (xsv_create picks 8 x 32 where that wastes fewer rows)
   int last_attend_wgs = 0;  // grid of the most recent attention launch
   // optional timing of the attention launches: events before, between the two kernels, after, and one more
   // right behind (the span of the last two, with nothing between them, is what an event pair itself costs)
@@ -196,14 +196,15 @@ int fill_batch(xsv_ctx* ctx, Batch& b, int layer0, int n_layers, const xsv_tenso
 }
 
 // The three stages for layers [layer0, layer0 + n_layers), which must be in step with each other.
+// frame_only: the frame's own tokens are the only keys (no cache tiles, no change of state).
 int do_attend(xsv_ctx* ctx, int layer0, int n_layers, const xsv_tensor* q, const xsv_tensor* k, const xsv_tensor* v,
-              void* const* out, int splits_req, int spare_cus) {
+              void* const* out, int splits_req, int spare_cus, bool frame_only = false) {
   AttendArgs a{};
   int rc = fill_batch(ctx, a.b, layer0, n_layers, q, k, v, out);
   if (rc != XSV_OK) return rc;
   a.pool = ctx->pool;
   a.ws = ctx->ws;
-  a.Tc = ctx->layers[layer0].T;
+  a.Tc = frame_only ? 0 : ctx->layers[layer0].T;
   a.n = ctx->cfg.tokens_per_frame;
   a.variant = ctx->attend_variant;
   AttendPlan plan = choose_grid(ctx, n_layers, a.Tc, splits_req, spare_cus);
@@ -248,7 +249,7 @@ int do_attend(xsv_ctx* ctx, int layer0, int n_layers, const xsv_tensor* q, const
   if (launch_attend(a, ctx->stream, ev[1]) != hipSuccess) return hip_fail(ctx);
   if (ev[2] && (hipEventRecord(ev[2], ctx->stream) != hipSuccess || hipEventRecord(ev[3], ctx->stream) != hipSuccess))
     return hip_fail(ctx);
-  for (int i = 0; i < n_layers; ++i) ctx->layers[layer0 + i].phase = kAttended;
+  for (int i = 0; i < n_layers && !frame_only; ++i) ctx->layers[layer0 + i].phase = kAttended;
   return XSV_OK;
 }
 
@@ -395,6 +396,9 @@ int xsv_create(const xsv_config* cfg, void* hip_stream, xsv_ctx** out) {
     delete ctx;
     return XSV_ERR_HIP;
   }
+  // workgroups of 512 query rows unless blocks of 256 leave fewer padding rows in a frame's last block
+  // (1041 tokens: 1280 against 1536 rows)
+  ctx->attend_variant = round_up(c.tokens_per_frame, 256) < round_up(c.tokens_per_frame, 512) ? 2 : 3;
   ctx->pending.assign(c.n_layers, -1);
   for (int l = 0; l < c.n_layers; ++l) {
     hipEvent_t e = nullptr;
@@ -573,6 +577,14 @@ int xsv_dequant_attend(xsv_ctx* ctx, int layer, xsv_tensor q, xsv_tensor k_new, 
   if ((rc = join_layers(ctx, layer, 1)) != XSV_OK) return rc;
   void* outs[1] = {out};
   return do_attend(ctx, layer, 1, &q, &k_new, &v_new, outs, ctx->splits_single, 0);
+}
+
+int xsv_frame_attend(xsv_ctx* ctx, xsv_tensor q, xsv_tensor k, xsv_tensor v, void* out) {
+  if (!ctx) return XSV_ERR_ARG;
+  if (ctx->broken) return XSV_ERR_HIP;
+  if (!tensor_ok(q) || !tensor_ok(k) || !tensor_ok(v) || !out) return XSV_ERR_ARG;
+  void* outs[1] = {out};
+  return do_attend(ctx, 0, 1, &q, &k, &v, outs, ctx->splits_single, 0, true);
 }
 
 int xsv_score_prune(xsv_ctx* ctx, int layer, xsv_tensor q) {

@@ -7,6 +7,7 @@ per-frame cost stay constant; Sec. 4.4 reports the same comparison on video stre
     python -m paper_2602_21780_amd.stream_report --long 200
     python -m paper_2602_21780_amd.stream_report --granularity
     python -m paper_2602_21780_amd.stream_report --selector-sweep
+    python -m paper_2602_21780_amd.stream_report --frame-attention
 
 `--configs`: frames/s of each listed workload at its saturated cache, layer by layer through xsv_step
 (overlap mode 2, one xsv_join per frame), events on the launch stream around each frame's 24 (or 1) steps.
@@ -20,6 +21,8 @@ unbounded bf16 cache; prints the relative RMS difference of the attention output
 saturation) for token budgets 2748 (first + current only) .. 8192, pooling sizes 4 / 16 / 64, the per-head
 selector (score_mode 1), pruning without quantization and quantization without pruning — the analogue of the
 paper's cache-length ablation (Sec. 4.5) with output error standing in for the task metrics.
+`--frame-attention`: the frame-wise attention of the alternating backbone (xsv_frame_attend: a frame's tokens over
+themselves) at 1374 and 1041 tokens, 16 heads: time per launch over 24 x 20 launches issued back to back.
 Inputs are synthetic (seeded), generated on the device outside the timed regions.  One JSON line per row.
 """
 from __future__ import annotations
@@ -125,6 +128,30 @@ def selector_sweep(torch, xsv, FrameSource, CONFIGS, frames=14):
     return rows
 
 
+def frame_attention(torch, xsv, FrameSource, CONFIGS, reps=20):
+    rows = []
+    for cid in (2, 4):
+        spec = CONFIGS[cid].with_(n_layers=1)
+        n, H = spec.tokens_per_frame, spec.n_heads
+        q, k, v = (t[0] for t in FrameSource(spec, "cuda:0", layers=[0]).frame(0))
+        ctx = xsv.Context.from_spec(spec)
+        out = torch.empty_like(q)
+        for _ in range(24):
+            ctx.frame_attend(q, k, v, out)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(24 * reps):
+            ctx.frame_attend(q, k, v, out)
+        e1.record()
+        torch.cuda.synchronize()
+        us = 1e3 * e0.elapsed_time(e1) / (24 * reps)
+        flop = 4.0 * n * n * H * spec.head_dim
+        rows.append({"kernel": "frame attention", "tokens": n, "heads": H, "us_per_launch": round(us, 2),
+                     "GFLOP": round(flop / 1e9, 2), "TFLOPs": round(flop / us / 1e6, 1), "workgroups": ctx.last_attend_workgroups()})
+        ctx.destroy()
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--configs", default="", help="comma-separated workload ids of inputs.CONFIGS")
@@ -133,6 +160,7 @@ def main():
                     help="for --configs: 0 = one retained set per layer (the paper's score), 1 = one per head")
     ap.add_argument("--long", type=int, default=0, help="frames of the long-stream comparison (0 = skip)")
     ap.add_argument("--granularity", action="store_true", help="per-token vs per-channel quantization error table")
+    ap.add_argument("--frame-attention", action="store_true", help="time the frame-wise attention entry point")
     ap.add_argument("--selector-sweep", action="store_true", help="output error against an uncompressed cache per variant")
     args = ap.parse_args()
 
@@ -158,6 +186,10 @@ def main():
 
     if args.granularity:
         for r in granularity_table(torch, xsv, FrameSource, CONFIGS):
+            print(json.dumps(r), flush=True)
+
+    if args.frame_attention:
+        for r in frame_attention(torch, xsv, FrameSource, CONFIGS):
             print(json.dumps(r), flush=True)
 
     if args.selector_sweep:

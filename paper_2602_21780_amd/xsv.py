@@ -41,7 +41,7 @@ class xsv_tensor(C.Structure):
 
 # every symbol include/xsv.h declares
 EXPORTS = (
-    "xsv_create", "xsv_destroy", "xsv_reset", "xsv_dequant_attend", "xsv_score_prune", "xsv_quantize",
+    "xsv_create", "xsv_destroy", "xsv_reset", "xsv_dequant_attend", "xsv_frame_attend", "xsv_score_prune", "xsv_quantize",
     "xsv_step", "xsv_step_all_layers", "xsv_set_attend_splits", "xsv_set_attend_variant", "xsv_set_overlap", "xsv_join", "xsv_set_side_cus", "xsv_set_short_range", "xsv_last_attend_workgroups", "xsv_set_attend_timing", "xsv_attend_times", "xsv_chain_times", "xsv_cache_len", "xsv_cache_export",
     "xsv_cache_import", "xsv_last_selection", "xsv_quantize_k", "xsv_quantize_v", "xsv_score",
     "xsv_topk_keep", "xsv_strerror",
@@ -65,6 +65,7 @@ def lib():
         L.xsv_reset.argtypes = [vp]
         L.xsv_join.argtypes = [vp]
         L.xsv_dequant_attend.argtypes = [vp, i32, T, T, T, vp]
+        L.xsv_frame_attend.argtypes = [vp, T, T, T, vp]
         L.xsv_score_prune.argtypes = [vp, i32, T]
         L.xsv_quantize.argtypes = [vp, i32, T, T]
         L.xsv_step.argtypes = [vp, i32, T, T, T, vp]
@@ -219,6 +220,11 @@ class Context:
         out = self._out(q, out)
         _check(lib().xsv_dequant_attend(self._h, layer, as_tensor(q), as_tensor(k_new), as_tensor(v_new), out.data_ptr()),
                "xsv_dequant_attend")
+        return out
+
+    def frame_attend(self, q, k, v, out=None):
+        out = self._out(q, out)
+        _check(lib().xsv_frame_attend(self._h, as_tensor(q), as_tensor(k), as_tensor(v), out.data_ptr()), "xsv_frame_attend")
         return out
 
     def score_prune(self, layer, q):

@@ -130,3 +130,26 @@ def test_topk_keep_all_equal_scores_take_smallest_positions():
     scores = torch.zeros(1000, device=DEV)
     keep = xsv.topk_keep(scores, 10, 0, 0).cpu().numpy()
     assert keep.tolist() == list(range(10))
+
+
+@pytest.mark.parametrize("H,n,splits", [(2, 64, 0), (3, 150, 2), (16, 1374, 0), (16, 1041, 0), (1, 1, 0)])
+def test_frame_attention_matches_oracle(H, n, splits):
+    """Attention inside one frame (no cache): the oracle's attention over the frame's own keys; the context's
+    streaming state is not touched."""
+    print(f"frame attention H={H} n={n}", flush=True)
+    q, k, v = (randn_bf16((H, n, 64), 3 * n + i, outliers=((5, 50) if i == 1 else ())) for i in range(3))
+    ctx = xsv.Context(1, H, 64, n, min(5, n), 4 * n, 4, 64)
+    ctx.set_attend_splits(splits, splits)
+    ctx.step(0, q, k, v)                         # a cached frame that frame attention must ignore
+    out = ctx.frame_attend(q, k, v)
+    rows = np.unique(np.array([0, n // 3, n // 2, n - 1], np.int32))
+    expect = ref.attend(to_u16(q), to_u16(k), to_u16(v), 0.125, rows=rows)
+    got = to_u16(out)[:, rows].astype(np.uint32) << 16
+    got = got.view(np.float32).astype(np.float64)
+    assert float(np.max(np.abs(got - expect))) <= 2e-2
+    rms = float(np.sqrt(np.mean((got - expect) ** 2)) / np.sqrt(np.mean(expect ** 2)))
+    assert rms <= 1e-2
+    assert ctx.cache_len(0) == n
+    ctx.step(0, q, k, v)                         # the stream goes on as if nothing had happened
+    assert ctx.cache_len(0) == 2 * n
+    ctx.destroy()

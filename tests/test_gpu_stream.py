@@ -105,6 +105,23 @@ def test_per_head_selection_batched_equals_per_layer_steps():
     ctx_b.destroy()
 
 
+@pytest.mark.parametrize("variant", [0, 1, 2, 3])
+@pytest.mark.parametrize("splits", [0, 3])
+def test_every_workgroup_shape_of_the_attention_kernel(variant, splits):
+    """4 x 64, 4 x 32, 8 x 32 and 8 x 64 query rows per workgroup on a stream whose frame is ragged for all of them."""
+    spec = CONFIGS[0].with_(name=f"shape{variant}", n_heads=3, tokens_per_frame=600, budget=2000, n_layers=1, group_size=64, seed=23)
+    ctx, st = parity.make_pair(spec)
+    ctx.set_attend_variant(variant)
+    ctx.set_attend_splits(splits, splits)
+    src = FrameSource(spec, DEV)
+    rows = np.array([0, 31, 32, 63, 64, 255, 256, 300, 511, 512, 575, 576, 599], np.int32)
+    for f in range(5):
+        q, k, v = src.frame(f)
+        print(f"  {spec.name} frame {f} T={ctx.cache_len(0)}", flush=True)
+        parity.step_and_compare(ctx, st, spec, 0, 0, q[0], k[0], v[0], rows=rows)
+    ctx.destroy()
+
+
 def test_budget_below_two_frames_keeps_first_and_current():
     spec = CONFIGS[0].with_(name="k0", budget=100)
     run_stream(spec, 4)
