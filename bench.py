@@ -26,6 +26,11 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes of one attend_kernel launch of this workload (fetch 30.3 MB + write 25.7 MB), from the two
 # rocprofv3 --pmc runs summarized in profiles/attend_cfg2_hbm_traffic.md; not measurable from inside this
 # process, so it is carried here and only reported for the grid it was measured on.
+# Vector instructions (wave level, rocprofv3 SQ_INSTS_VALU) of one requant_kernel launch over all 24 layers of this
+# workload, from profiles/requant_cfg2_valu_counters.md, and the chip's vector issue peak: 256 compute units x 4 SIMDs,
+# one instruction per 4 cycles at 2.4 GHz.
+REQUANT_VALU_CFG2_24_LAYERS = 86.57e6
+PEAK_VALU_GINSTR = 256 * 4 * 2.4 / 4.0
 TRAFFIC_ATTEND_CFG2 = {"workgroups": 240, "bytes": 56.0e6}
 
 
@@ -217,6 +222,11 @@ def main():
     }
     hbm["all_layers_per_launch"]["score_prune_frac"] = round(hbm["all_layers_per_launch"]["score_prune_GBs"] / PEAK_HBM_GBS, 4)
     hbm["all_layers_per_launch"]["quantize_frac"] = round(hbm["all_layers_per_launch"]["quantize_GBs"] / PEAK_HBM_GBS, 4)
+    if spec.name == "cfg2-24-layer" and rq_ms > 0:
+        ginstr = REQUANT_VALU_CFG2_24_LAYERS / (rq_ms * 1e-3) / 1e9
+        hbm["all_layers_per_launch"]["quantize_alu"] = {
+            "bound": "alu", "achieved": round(ginstr, 1), "peak": round(PEAK_VALU_GINSTR, 1),
+            "unit": "G vector instructions/s (wave level)", "frac": round(ginstr / PEAK_VALU_GINSTR, 4)}
 
     # ---- the oracle on the host cores, bounded sample ------------------------------------------------
     cpu = None
