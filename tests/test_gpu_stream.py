@@ -232,10 +232,12 @@ def test_same_inputs_twice_give_identical_bytes():
     assert np.array_equal(dumps[0][2][0], dumps[1][2][0]) and np.array_equal(dumps[0][2][1], dumps[1][2][1])
 
 
-def test_import_of_oracle_cache_then_attend():
-    """dequant_attend alone, on a cache produced by the oracle (isolates it from the GPU quantizer)."""
+@pytest.mark.parametrize("score_mode", [0, 1])
+def test_import_of_oracle_cache_then_attend(score_mode):
+    """dequant_attend alone, on a cache produced by the oracle (isolates it from the GPU quantizer); with per-head
+    selection the imported token ids are one row per head, and the stream continues from the imported state."""
     spec = CONFIGS[0].with_(name="import", n_heads=3, tokens_per_frame=100, budget=300, group_size=64)
-    ctx, st = parity.make_pair(spec)
+    ctx, st = parity.make_pair(spec, score_mode=score_mode)
     src = FrameSource(spec, DEV)
     for f in range(4):
         q, k, v = src.frame(f)
@@ -245,8 +247,12 @@ def test_import_of_oracle_cache_then_attend():
     parity.compare_cache(ctx.cache_export(0), c, True)
     q, k, v = src.frame(4)
     out = ctx.dequant_attend(0, q[0], k[0], v[0])
-    expect, _ = st.step(0, to_u16(q[0]), to_u16(k[0]), to_u16(v[0]))
+    ctx.score_prune(0, q[0])
+    ctx.quantize(0, k[0], v[0])
+    _, keep = ctx.last_selection(0)
+    expect, _ = st.step(0, to_u16(q[0]), to_u16(k[0]), to_u16(v[0]), forced_keep=keep)
     parity.check_attention(to_u16(out), expect)
+    parity.compare_cache(ctx.cache_export(0), st.export(0), True)     # token ids travelled through the import
     ctx.destroy()
 
 
