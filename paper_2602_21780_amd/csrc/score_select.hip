@@ -3,9 +3,9 @@
 // The importance  S_j = (1/N_pooled) sum_i (Qbar Kbar^T)[i][j]  is linear in the pooled queries, so
 // it is evaluated as  S_j = qtilde . Kbar_j  with  qtilde = (1/N_pooled) sum_i Qbar_i :
 //   pool_query_kernel   one pass over Q: weighted row sums (weight 1/(H N_pooled) for a special
-//                       row, 1/(H N_pooled |group|) for a patch row), one workgroup and one
-//                       partial per head; every score workgroup adds the H partials in head order,
-//                       so the result is reproducible bit for bit and needs no atomics.
+//                       row, 1/(H N_pooled |group|) for a patch row), kPoolSeg workgroups (row segments)
+//                       and partials per head; every score workgroup adds the partials in a fixed
+//                       order, so the result is reproducible bit for bit and needs no atomics.
 //   score_kernel        one pass over the packed keys of the prunable middle: dequantized view,
 //                       head mean, dot product with qtilde.  64 tokens x all heads per workgroup,
 //                       16 channels per thread, all loads of a workgroup issued before any use.
@@ -27,19 +27,21 @@ __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w 
 
 constexpr int kPoolThreads = 1024;
 
-// grid (H, layers), 1024 threads: thread = (row lane tid/8 of 128, channel run tid%8).  One partial
-// weighted row sum [64] per head; the score kernel adds the H partials in head order.
+// grid (H * kPoolSeg, layers), 1024 threads: thread = (row lane tid/8 of 128, channel run tid%8); a workgroup
+// takes one of kPoolSeg row segments of one head.  One partial weighted row sum [64] per (head, segment);
+// the score kernel adds the partials in (head, segment) order.
 __global__ __launch_bounds__(kPoolThreads) void pool_query_kernel(const ScoreArgs a) {
   __shared__ float red[kPoolThreads / 8][kD + 1];
-  const int lb = blockIdx.y, h = blockIdx.x;
+  const int lb = blockIdx.y, h = blockIdx.x / kPoolSeg, seg = blockIdx.x % kPoolSeg;
   const int H = a.pool.H, n = a.n, n_s = a.n_special, g = a.pool_size;
+  const int seg_rows = (n + kPoolSeg - 1) / kPoolSeg, r_end = min(n, (seg + 1) * seg_rows);
   const int n_pooled = n_s + (n - n_s + g - 1) / g;
   const int tid = threadIdx.x, rl = tid >> 3, o = tid & 7;
   const uint16_t* qh = a.b.q[lb] + (size_t)h * a.b.q_sh;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   const float base = a.per_head ? (float)n_pooled : (float)(H * n_pooled);
 #pragma unroll 4
-  for (int r = rl; r < n; r += kPoolThreads / 8) {
+  for (int r = seg * seg_rows + rl; r < r_end; r += kPoolThreads / 8) {
     float w;
     if (r < n_s) {
       w = 1.0f / base;
@@ -60,22 +62,22 @@ __global__ __launch_bounds__(kPoolThreads) void pool_query_kernel(const ScoreArg
   for (int e = 0; e < 8; ++e) red[rl][o * 8 + e] = acc[e];
   __syncthreads();
   // fold the 128 row lanes in a fixed order: 4 segments of 32, then a chain
-  __shared__ float seg[4][kD];
+  __shared__ float seg4[4][kD];
   if (tid < 4 * kD) {
     const int sg = tid >> 6, c = tid & 63;
     float s = 0.f;
     for (int i = sg * 32; i < sg * 32 + 32; ++i) s += red[i][c];
-    seg[sg][c] = s;
+    seg4[sg][c] = s;
   }
   __syncthreads();
   if (tid < kD) {
     float* part = a.ws.qpart + (size_t)(a.b.layer0 + lb) * a.ws.qpart_rows * kD;
-    part[(size_t)h * kD + tid] = ((seg[0][tid] + seg[1][tid]) + seg[2][tid]) + seg[3][tid];
+    part[(size_t)blockIdx.x * kD + tid] = ((seg4[0][tid] + seg4[1][tid]) + seg4[2][tid]) + seg4[3][tid];
   }
 }
 
 hipError_t launch_pool_query(const ScoreArgs& a, hipStream_t stream) {
-  hipLaunchKernelGGL(pool_query_kernel, dim3(a.pool.H, a.b.n_layers), dim3(kPoolThreads), 0, stream, a);
+  hipLaunchKernelGGL(pool_query_kernel, dim3(a.pool.H * kPoolSeg, a.b.n_layers), dim3(kPoolThreads), 0, stream, a);
   return hipGetLastError();
 }
 
@@ -112,13 +114,15 @@ __global__ __launch_bounds__(256) void score_kernel(const ScoreArgs a) {
     head_stride = (size_t)a.pool.Tcap * kRowDw;
   }
   const float* part = a.ws.qpart + (size_t)(a.b.layer0 + lb) * a.ws.qpart_rows * kD;
-  if (!PER_HEAD && tid < kD) {  // the H partial sums, in head order
-    float s = 0.f;
-#pragma unroll 16
-    for (int h = 0; h < H; ++h) s += part[(size_t)h * kD + tid];
-    qtilde[tid] = s;
-  }
 
+  auto fold_partials = [&]() {  // the H partial query sums, in head order (called once, behind the chunk's loads)
+    if (!PER_HEAD && tid < kD) {
+      float s = 0.f;
+#pragma unroll 16
+      for (int h = 0; h < H * kPoolSeg; ++h) s += part[(size_t)h * kD + tid];
+      qtilde[tid] = s;
+    }
+  };
   float acc[16];
 #pragma unroll
   for (int e = 0; e < 16; ++e) acc[e] = 0.f;
@@ -132,17 +136,32 @@ __global__ __launch_bounds__(256) void score_kernel(const ScoreArgs a) {
       for (int i = 0; i < kDwT; ++i) w[h][i] = (valid && h < hn) ? src[(h0 + h) * head_stride + i] : 0u;
     if constexpr (PER_HEAD) {
       if (h0 > 0) __syncthreads();  // the previous chunk's rows are no longer read
-      for (int i = tid; i < hn * kD; i += 256) qtilde[i] = part[(size_t)h0 * kD + i];
+      for (int i = tid; i < hn * kD; i += 256) {  // head h0 + i / 64: its segments in order
+        const float* ph = part + ((size_t)(h0 + i / kD) * kPoolSeg) * kD + i % kD;
+        float s = ph[0];
+#pragma unroll
+        for (int sg = 1; sg < kPoolSeg; ++sg) s += ph[sg * kD];
+        qtilde[i] = s;
+      }
     }
     if constexpr (kQuant) {
       const LayerCache lc = layer_cache(a.pool, a.b.src_buf(lb), a.b.layer0 + lb);
       const int gcap = a.pool.Tcap / G;
-      if (h0 > 0 && !PER_HEAD) __syncthreads();  // the previous chunk's parameters are no longer read
-      for (int i = tid; i < hn * kGroups * 2 * kD; i += 256) {
+      constexpr int kPrmIter = HMAX * kGroups * 2 * kD / 256;
+      float pr[kPrmIter];  // loaded first, stored to LDS below: every load is in flight before the first wait
+#pragma unroll
+      for (int it = 0; it < kPrmIter; ++it) {
+        const int i = tid + it * 256;
         const int c = i % kD, sz = (i / kD) & 1, gi = (i / (2 * kD)) % kGroups, h = i / (2 * kD * kGroups);
         const float* p = sz ? lc.kz : lc.ks;
-        prm[i] = p[((size_t)(h0 + h) * gcap + block * kGroups + gi) * kD + c];
+        pr[it] = h < hn ? p[((size_t)(h0 + h) * gcap + block * kGroups + gi) * kD + c] : 0.f;
       }
+      if (h0 == 0) fold_partials();
+      if (h0 > 0 && !PER_HEAD) __syncthreads();  // the previous chunk's parameters are no longer read
+#pragma unroll
+      for (int it = 0; it < kPrmIter; ++it) prm[tid + it * 256] = pr[it];
+    } else {
+      if (h0 == 0) fold_partials();
     }
     __syncthreads();
 #pragma unroll

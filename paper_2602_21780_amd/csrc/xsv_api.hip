@@ -440,7 +440,7 @@ int xsv_create(const xsv_config* cfg, void* hip_stream, xsv_ctx** out) {
   Workspace& w = ctx->ws;
   std::memset(&w, 0, sizeof(w));
   w.scores_stride = p.Tcap + (int)n;
-  w.qpart_rows = c.n_heads;
+  w.qpart_rows = c.n_heads * kPoolSeg;
   w.sets = p.sets;
   A(&w.scores, (size_t)c.n_layers * w.sets * w.scores_stride, true);
   A(&w.keep, (size_t)c.n_layers * w.sets * w.scores_stride, true);
@@ -905,7 +905,7 @@ int xsv_score(void* hip_stream, xsv_tensor q, const void* k_mid_bf16, int H, int
   s.b.n_layers = 1; s.b.layer0 = 0;
   s.b.q[0] = static_cast<const uint16_t*>(q.ptr);
   s.b.q_sh = q.stride_head; s.b.q_st = q.stride_token;
-  s.ws.qpart_rows = H;
+  s.ws.qpart_rows = H * kPoolSeg;
   s.ws.sets = 1;
   s.ws.qpart = tmp.get<float>((size_t)s.ws.qpart_rows * kD);
   if (!s.ws.qpart) return XSV_ERR_OOM;

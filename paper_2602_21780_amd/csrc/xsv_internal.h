@@ -21,6 +21,10 @@ namespace xsv {
 constexpr int kD = 64;         // head_dim
 constexpr int kTile = 64;      // tokens per value block and per attention key tile
 constexpr int kMaxBatch = 32;  // layers per batched launch
+// Row segments (workgroups) per head of the pooled-query pass.  One: beside the attention launch of a step
+// only a few compute units are idle when the chain starts, and with four segments (3 us faster alone) the
+// extra workgroups wait for units and the step as a whole gets 1.6 % slower.
+constexpr int kPoolSeg = 1;
 
 struct CachePool {
   uint8_t* kc;
@@ -92,7 +96,7 @@ struct Batch {
 struct Workspace {
   float* scores;      // [L][sets][Tcap + n]  importance of the middle tokens
   int32_t* keep;      // [L][sets][Tcap + n]  keep list
-  float* qpart;       // [L][qpart_rows][64] partial weighted query sums
+  float* qpart;       // [L][qpart_rows = H * kPoolSeg][64] partial weighted query sums
   uint16_t* attn_o;   // [pieces][batch layers][H][ceil(n/32)] blocks of 32 rows x 64 fp16 mantissas of the unnormalized
                       // partial outputs, each block stored [16-byte piece 0..3][lane half][row] (4 KB)
   float* attn_ml;     // [pieces][batch layers][H][n][4]  softmax reference (log2 domain), row sum, row scale, -
