@@ -348,6 +348,26 @@ def test_degenerate_and_smallest_shapes(n, n_s, H, budget, bits, G):
     run_stream(spec, 7)
 
 
+@pytest.mark.parametrize("n,n_s,H,budget,bits,G,g,mode", [
+    (79, 0, 3, 200, 4, 32, 3, 0),
+    (122, 1, 2, 300, 16, 64, 1, 0),
+    (282, 4, 5, 700, 4, 32, 1, 1),
+    (25, 5, 2, 77, 2, 64, 1, 0),
+    (317, 1, 1, 820, 4, 64, 3, 0),
+    (90, 4, 5, 250, 4, 64, 16, 1),
+    (122, 2, 4, 0, 2, 64, 16, 1),      # unbounded, quantized
+    (195, 1, 4, 500, 2, 32, 7, 0),
+    (60, 4, 3, 107, 4, 64, 16, 0),     # budget below first + current
+    (10, 1, 2, 25, 16, 32, 1, 1),
+    (300, 5, 2, 1000, 2, 64, 16, 0),
+])
+def test_assorted_shapes_and_settings(n, n_s, H, budget, bits, G, g, mode):
+    """Frame sizes, head counts, budgets, pooling sizes and selectors that are no multiples of anything."""
+    spec = CONFIGS[0].with_(name=f"mix-n{n}-h{H}", n_heads=H, tokens_per_frame=n, n_special=n_s, budget=budget, kv_bits=bits,
+                            group_size=G, pool_size=g, n_layers=2, seed=100 + n, frames=8)
+    run_stream(spec, 7, score_mode=mode)
+
+
 def test_step_can_be_captured_in_a_graph_and_replayed():
     """xsv_step enqueues only kernels and event record/wait pairs, so a stream capture takes it whole (the
     side stream joins the capture through the fork event and leaves it through the join event).  A replay
