@@ -250,6 +250,12 @@ def main():
                          f"{n_timed * t_step:.1f} s in all; a frame is {L} such steps"}
         st.close()
 
+    # the device's own yardsticks: a loop of nothing but the attention kernel's MFMA instruction, a plain copy
+    mfma_peak, copy_peak = xsv.measure_peaks()
+    roofline["measured_mfma_loop_TFLOPs"] = round(mfma_peak, 1)
+    roofline["frac_of_measured_mfma_loop"] = round(attend_tflops / mfma_peak, 4)
+    hbm["measured_copy_GBs"] = round(copy_peak, 1)
+
     result = {
         "metric": "streamed frames/s for 24-layer compressed global-attn step",
         "value": round(value, 2), "unit": "frames/s", "n_gpus": 1, "steps": K, "warmup": W,

@@ -221,6 +221,11 @@ int xsv_score(void* hip_stream, xsv_tensor q, const void* k_mid_bf16, int H, int
  * ascending; keep: int32 [T_first + k + T_cur]. */
 int xsv_topk_keep(void* hip_stream, const float* scores, int P, int k, int T_first, int T_cur, int32_t* keep);
 
+/* Measurement aid, synchronous: two yardsticks of the current device - the rate of a loop of nothing but the bf16
+ * MFMA instruction the attention kernel uses (TFLOP/s, all compute units busy) and of a plain streaming copy of
+ * 512 MiB (GB/s, bytes read + bytes written).  Allocates and frees 1 GiB of temporaries; takes about 50 ms. */
+int xsv_measure_peaks(void* hip_stream, float* mfma_bf16_tflops, float* copy_gbs);
+
 const char* xsv_strerror(int code);
 
 #ifdef __cplusplus

@@ -22,6 +22,7 @@ SOURCES = {
     "attend.hip": ["-fno-honor-nans", "-mllvm", "-amdgpu-mfma-vgpr-form=1"],
     "score_select.hip": ["-ffp-contract=off"],
     "requant.hip": ["-ffp-contract=off"],
+    "peaks.hip": [],
 }
 
 

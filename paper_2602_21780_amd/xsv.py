@@ -44,7 +44,7 @@ EXPORTS = (
     "xsv_create", "xsv_destroy", "xsv_reset", "xsv_dequant_attend", "xsv_frame_attend", "xsv_score_prune", "xsv_quantize",
     "xsv_step", "xsv_step_all_layers", "xsv_set_attend_splits", "xsv_set_attend_variant", "xsv_set_overlap", "xsv_join", "xsv_set_side_cus", "xsv_set_short_range", "xsv_last_attend_workgroups", "xsv_set_attend_timing", "xsv_attend_times", "xsv_chain_times", "xsv_cache_len", "xsv_cache_export",
     "xsv_cache_import", "xsv_last_selection", "xsv_quantize_k", "xsv_quantize_v", "xsv_score",
-    "xsv_topk_keep", "xsv_strerror",
+    "xsv_topk_keep", "xsv_measure_peaks", "xsv_strerror",
 )
 
 _lib = None
@@ -87,6 +87,7 @@ def lib():
         L.xsv_quantize_v.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp, vp]
         L.xsv_score.argtypes = [vp, T, vp, i32, i32, i32, i32, i32, i32, vp]
         L.xsv_topk_keep.argtypes = [vp, vp, i32, i32, i32, i32, vp]
+        L.xsv_measure_peaks.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_float)]
         L.xsv_strerror.argtypes = [i32]
         L.xsv_strerror.restype = C.c_char_p
         for name in EXPORTS:
@@ -340,3 +341,10 @@ def topk_keep(scores, k, T_first, T_cur, stream=None):
     _check(lib().xsv_topk_keep(_stream_ptr(stream), scores.data_ptr() if P else None, P, k, T_first, T_cur,
                                keep.data_ptr()), "xsv_topk_keep")
     return keep
+
+
+def measure_peaks(stream=None):
+    """(bf16 MFMA loop TFLOP/s, streaming copy GB/s) of the current device."""
+    a, b = C.c_float(), C.c_float()
+    _check(lib().xsv_measure_peaks(_stream_ptr(stream), C.byref(a), C.byref(b)), "xsv_measure_peaks")
+    return a.value, b.value

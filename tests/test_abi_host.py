@@ -62,6 +62,7 @@ def test_null_context_is_rejected(lib):
     assert lib.xsv_quantize_k(None, None, 1, 1, 64, 4, 64, None, None, None) == xsv.XSV_ERR_ARG
     assert lib.xsv_topk_keep(None, None, 4, 5, 0, 0, None) == xsv.XSV_ERR_ARG
     assert lib.xsv_join(None) == xsv.XSV_ERR_ARG
+    assert lib.xsv_measure_peaks(None, None, None) == xsv.XSV_ERR_ARG
     assert lib.xsv_frame_attend(None, t, t, t, None) == xsv.XSV_ERR_ARG
     assert lib.xsv_set_overlap(None, 1) == xsv.XSV_ERR_ARG
     assert lib.xsv_set_side_cus(None, 0) == xsv.XSV_ERR_ARG

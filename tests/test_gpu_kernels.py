@@ -153,3 +153,11 @@ def test_frame_attention_matches_oracle(H, n, splits):
     ctx.step(0, q, k, v)                         # the stream goes on as if nothing had happened
     assert ctx.cache_len(0) == 2 * n
     ctx.destroy()
+
+
+def test_measured_peaks_are_plausible():
+    """The library's two yardsticks: an MFMA-only loop and a streaming copy, against the published peaks."""
+    mfma, copy = xsv.measure_peaks()
+    print(f"measured: MFMA loop {mfma:.0f} TFLOP/s, copy {copy:.0f} GB/s", flush=True)
+    assert 800.0 < mfma < 2600.0
+    assert 1500.0 < copy < 8200.0
