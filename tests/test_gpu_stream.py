@@ -276,6 +276,37 @@ def test_call_order_is_enforced():
     ctx.destroy()
 
 
+def test_bad_arguments_are_rejected_before_anything_is_launched():
+    """Misaligned or too narrow tensors, a NULL output, a cache that cannot hold another frame: error codes, and
+    the context goes on working afterwards."""
+    import ctypes as C
+    spec = CONFIGS[0].with_(budget=0)
+    n = spec.tokens_per_frame
+    ctx = xsv.Context.from_spec(spec, max_frames=2)
+    lib = xsv.lib()
+    q, k, v = (t[0] for t in FrameSource(spec, DEV).frame(0))
+    out = torch.empty_like(q)
+    T = xsv.as_tensor
+    odd = xsv.xsv_tensor(q.data_ptr() + 2, q.stride(0), q.stride(1))           # not 16-byte aligned
+    narrow = xsv.xsv_tensor(q.data_ptr(), q.stride(0), 32)                      # rows overlap
+    for bad in (odd, narrow, xsv.xsv_tensor(None, 0, 64)):
+        assert lib.xsv_step(ctx._h, 0, bad, T(k), T(v), out.data_ptr()) == xsv.XSV_ERR_ARG
+        assert lib.xsv_step(ctx._h, 0, T(q), bad, T(v), out.data_ptr()) == xsv.XSV_ERR_ARG
+        assert lib.xsv_frame_attend(ctx._h, T(q), T(k), bad, out.data_ptr()) == xsv.XSV_ERR_ARG
+    assert lib.xsv_step(ctx._h, 0, T(q), T(k), T(v), None) == xsv.XSV_ERR_ARG
+    assert ctx.cache_len(0) == 0                                                # nothing happened
+    ctx.step(0, q, k, v, out)
+    ctx.step(0, q, k, v, out)
+    assert ctx.cache_len(0) == 2 * n
+    assert lib.xsv_step(ctx._h, 0, T(q), T(k), T(v), out.data_ptr()) == xsv.XSV_ERR_STATE   # room for max_frames = 2 only
+    assert lib.xsv_dequant_attend(ctx._h, 0, T(q), T(k), T(v), out.data_ptr()) == xsv.XSV_ERR_STATE
+    ctx.reset()
+    ctx.step(0, q, k, v, out)
+    torch.cuda.synchronize()
+    assert ctx.cache_len(0) == n
+    ctx.destroy()
+
+
 def test_one_layer_config_full_size_sampled_rows():
     """cfg 1 at its real shape (16 heads, 1374 tokens, budget 2048 < first + current, so k = 0):
     cache bytes compared in full, attention on sampled query rows incl. the ragged last tile."""
