@@ -83,6 +83,11 @@ inline float dequantize_one(uint8_t code, float s, float z) {
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
+// memcpy that tolerates empty ranges (an empty cache has no storage to point at)
+inline void copy_bytes(void* dst, const void* src, size_t n) {
+  if (n != 0) std::memcpy(dst, src, n);
+}
+
 }  // namespace
 
 extern "C" {
@@ -380,8 +385,8 @@ void xsv_ref_cache_view(const xsv_ref_state* st, int layer, uint16_t* k_out, uin
   const size_t count = static_cast<size_t>(c.n_heads) * L.T * c.head_dim;
   if (L.T == 0) return;
   if (c.kv_bits == 16) {
-    std::memcpy(k_out, L.k_bf16.data(), count * 2);
-    std::memcpy(v_out, L.v_bf16.data(), count * 2);
+    copy_bytes(k_out, L.k_bf16.data(), count * 2);
+    copy_bytes(v_out, L.v_bf16.data(), count * 2);
   } else {
     xsv_ref_dequantize_k(L.k_codes.data(), L.k_scale.data(), L.k_zero.data(), c.n_heads, L.T, c.head_dim,
                          c.group_size, k_out);
@@ -415,13 +420,13 @@ int xsv_ref_step(xsv_ref_state* st, int layer, const uint16_t* q, const uint16_t
     std::vector<uint16_t> k_view(static_cast<size_t>(H) * Tc * d), v_view(static_cast<size_t>(H) * Tc * d);
     xsv_ref_cache_view(st, layer, k_view.data(), v_view.data());
     for (int h = 0; h < H; ++h) {
-      std::memcpy(&k_all[static_cast<size_t>(h) * T * d], &k_view[static_cast<size_t>(h) * Tc * d],
+      copy_bytes(k_all.data() + static_cast<size_t>(h) * T * d, k_view.data() + static_cast<size_t>(h) * Tc * d,
                   static_cast<size_t>(Tc) * d * 2);
-      std::memcpy(&v_all[static_cast<size_t>(h) * T * d], &v_view[static_cast<size_t>(h) * Tc * d],
+      copy_bytes(v_all.data() + static_cast<size_t>(h) * T * d, v_view.data() + static_cast<size_t>(h) * Tc * d,
                   static_cast<size_t>(Tc) * d * 2);
-      std::memcpy(&k_all[(static_cast<size_t>(h) * T + Tc) * d], &k_new[static_cast<size_t>(h) * n * d],
+      copy_bytes(k_all.data() + (static_cast<size_t>(h) * T + Tc) * d, &k_new[static_cast<size_t>(h) * n * d],
                   static_cast<size_t>(n) * d * 2);
-      std::memcpy(&v_all[(static_cast<size_t>(h) * T + Tc) * d], &v_new[static_cast<size_t>(h) * n * d],
+      copy_bytes(v_all.data() + (static_cast<size_t>(h) * T + Tc) * d, &v_new[static_cast<size_t>(h) * n * d],
                   static_cast<size_t>(n) * d * 2);
     }
   }
@@ -457,12 +462,12 @@ int xsv_ref_step(xsv_ref_state* st, int layer, const uint16_t* q, const uint16_t
         if (c.score_mode == 0) {
           std::vector<uint16_t> k_mid(static_cast<size_t>(H) * P * d);
           for (int h = 0; h < H; ++h)
-            std::memcpy(&k_mid[static_cast<size_t>(h) * P * d], &k_all[(static_cast<size_t>(h) * T + T_first) * d],
+            copy_bytes(k_mid.data() + static_cast<size_t>(h) * P * d, k_all.data() + (static_cast<size_t>(h) * T + T_first) * d,
                         static_cast<size_t>(P) * d * 2);
           xsv_ref_score(q, k_mid.data(), H, n, c.n_special, P, d, c.pool_size, scores.data());
         } else {
           // head s alone: the same score with "all heads" = this one head
-          xsv_ref_score(q + static_cast<size_t>(s) * n * d, &k_all[(static_cast<size_t>(s) * T + T_first) * d], 1, n,
+          xsv_ref_score(q + static_cast<size_t>(s) * n * d, k_all.data() + (static_cast<size_t>(s) * T + T_first) * d, 1, n,
                         c.n_special, P, d, c.pool_size, scores.data());
         }
         L.last_scores.insert(L.last_scores.end(), scores.begin(), scores.end());
@@ -485,8 +490,8 @@ int xsv_ref_step(xsv_ref_state* st, int layer, const uint16_t* q, const uint16_t
   for (int h = 0; h < H; ++h) {
     const std::vector<int32_t>& kp = keep[sets == 1 ? 0 : h];
     for (int i = 0; i < Tn; ++i) {
-      std::memcpy(&k_kept[(static_cast<size_t>(h) * Tn + i) * d], &k_all[(static_cast<size_t>(h) * T + kp[i]) * d], d * 2);
-      std::memcpy(&v_kept[(static_cast<size_t>(h) * Tn + i) * d], &v_all[(static_cast<size_t>(h) * T + kp[i]) * d], d * 2);
+      copy_bytes(k_kept.data() + (static_cast<size_t>(h) * Tn + i) * d, k_all.data() + (static_cast<size_t>(h) * T + kp[i]) * d, d * 2);
+      copy_bytes(v_kept.data() + (static_cast<size_t>(h) * Tn + i) * d, v_all.data() + (static_cast<size_t>(h) * T + kp[i]) * d, d * 2);
     }
   }
   std::vector<int32_t> tf(static_cast<size_t>(sets) * Tn), ti(static_cast<size_t>(sets) * Tn);
@@ -531,7 +536,7 @@ void xsv_ref_export(const xsv_ref_state* st, int layer, uint8_t* k_codes, float*
                     int32_t* token_frame, int32_t* token_index, float* last_scores, int32_t* last_keep) {
   const RefLayer& L = st->layers[layer];
   auto cp = [](auto* dst, const auto& src) {
-    if (dst && !src.empty()) std::memcpy(dst, src.data(), src.size() * sizeof(src[0]));
+    if (dst && !src.empty()) copy_bytes(dst, src.data(), src.size() * sizeof(src[0]));
   };
   cp(k_codes, L.k_codes);
   cp(k_scale, L.k_scale);
