@@ -19,6 +19,10 @@ namespace {
 
 enum Phase { kIdle = 0, kAttended = 1, kScored = 2 };
 
+// The fork / join events only order the context's two streams on one device: no timing, and no system-scope
+// fence (nothing here is read by the host or by another device at these points).
+constexpr unsigned kOrderingEvent = hipEventDisableTiming | hipEventDisableSystemFence;
+
 struct LayerState {
   int T = 0;        // cached tokens
   int frames = 0;   // frames seen
@@ -388,8 +392,8 @@ int xsv_create(const xsv_config* cfg, void* hip_stream, xsv_ctx** out) {
   ctx->work = ctx->stream;
   ctx->layers.resize(c.n_layers);
   if (hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) != hipSuccess ||
-      hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming) != hipSuccess ||
-      hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming) != hipSuccess) {
+      hipEventCreateWithFlags(&ctx->ev_fork, kOrderingEvent) != hipSuccess ||
+      hipEventCreateWithFlags(&ctx->ev_join, kOrderingEvent) != hipSuccess) {
     if (ctx->side) (void)hipStreamDestroy(ctx->side);
     if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
     if (ctx->ev_join) (void)hipEventDestroy(ctx->ev_join);
@@ -402,7 +406,7 @@ int xsv_create(const xsv_config* cfg, void* hip_stream, xsv_ctx** out) {
   ctx->pending.assign(c.n_layers, -1);
   for (int l = 0; l < c.n_layers; ++l) {
     hipEvent_t e = nullptr;
-    if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) {
+    if (hipEventCreateWithFlags(&e, kOrderingEvent) != hipSuccess) {
       free_all(ctx);
       delete ctx;
       return XSV_ERR_HIP;

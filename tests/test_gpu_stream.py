@@ -213,6 +213,39 @@ def test_deferred_join_gives_the_same_bytes_as_one_stream(batched):
     ctx_b.destroy()
 
 
+def test_free_running_overlapped_stream_equals_one_stream_at_full_size():
+    """The 24-layer workload for 12 frames without any host synchronization, chain on the second stream with
+    deferred joins (the form bench.py times), against the same stream on one stream: every output of the last
+    three frames and the caches of three layers must be the same bytes.  (The events that order the two streams
+    carry no system-scope fence; this is the check that device-scope ordering is enough.)"""
+    spec = CONFIGS[2]
+    L = spec.n_layers
+    src = FrameSource(spec, DEV)
+    frames = [src.frame(f) for f in range(12)]
+    results = []
+    for mode in (0, 2):
+        ctx = xsv.Context.from_spec(spec)
+        ctx.set_overlap(mode)
+        ctx.set_attend_splits(4, 4)      # the same key ranges in both runs, so that the outputs round alike
+        outs = torch.empty((3, L, spec.n_heads, spec.tokens_per_frame, spec.head_dim), dtype=torch.bfloat16, device=DEV)
+        scratch = torch.empty_like(outs[0])
+        for f, (q, k, v) in enumerate(frames):
+            dst = outs[f - 9] if f >= 9 else scratch
+            for l in range(L):
+                ctx.step(l, q[l], k[l], v[l], dst[l])
+            if mode == 2:
+                ctx.join()
+        torch.cuda.synchronize()
+        results.append((outs, [ctx.cache_export(l) for l in (0, 11, 23)], [ctx.last_selection(l)[1] for l in (0, 11, 23)]))
+        ctx.destroy()
+    (oa, ca, ka), (ob, cb, kb) = results
+    assert torch.equal(oa, ob)
+    for x, y in zip(ca, cb):
+        parity.compare_cache(x, y, True)
+    for x, y in zip(ka, kb):
+        assert np.array_equal(x, y)
+
+
 def test_same_inputs_twice_give_identical_bytes():
     spec = CONFIGS[0].with_(name="determinism", n_heads=4, tokens_per_frame=150, budget=400, group_size=64)
     dumps = []
