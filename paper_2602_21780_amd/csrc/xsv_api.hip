@@ -48,6 +48,9 @@ struct xsv_ctx {
   // pending[l] >= 0 names the event `stream` still has to wait for before it may touch layer l
   std::vector<hipEvent_t> ev_chain;
   std::vector<int> pending;
+  // the side stream is in order, so a later record implies every earlier one: seq[e] numbers the records
+  std::vector<long long> seq;
+  long long next_seq = 1;
   CachePool pool;
   Workspace ws;
   std::vector<LayerState> layers;
@@ -113,16 +116,18 @@ void free_all(xsv_ctx* ctx) {
   ctx->ev_fork = ctx->ev_join = nullptr;
 }
 
-// Orders the context's stream after the side-stream work still outstanding for layers [l0, l0 + n).
+// Orders the context's stream after the side-stream work still outstanding for layers [l0, l0 + n): ONE wait, for
+// the latest of their records (the side stream runs in order), which also settles every layer recorded before it.
 int join_layers(xsv_ctx* ctx, int l0, int n) {
-  int last = -1;
+  int latest = -1;
   for (int l = l0; l < l0 + n; ++l) {
     const int e = ctx->pending[l];
-    if (e < 0) continue;
-    if (e != last && hipStreamWaitEvent(ctx->stream, ctx->ev_chain[e], 0) != hipSuccess) return hip_fail(ctx);
-    last = e;
-    ctx->pending[l] = -1;
+    if (e >= 0 && (latest < 0 || ctx->seq[e] > ctx->seq[latest])) latest = e;
   }
+  if (latest < 0) return XSV_OK;
+  if (hipStreamWaitEvent(ctx->stream, ctx->ev_chain[latest], 0) != hipSuccess) return hip_fail(ctx);
+  for (int& e : ctx->pending)
+    if (e >= 0 && ctx->seq[e] <= ctx->seq[latest]) e = -1;
   return XSV_OK;
 }
 
@@ -404,6 +409,7 @@ int xsv_create(const xsv_config* cfg, void* hip_stream, xsv_ctx** out) {
   // (1041 tokens: 1280 against 1536 rows)
   ctx->attend_variant = round_up(c.tokens_per_frame, 256) < round_up(c.tokens_per_frame, 512) ? 2 : 3;
   ctx->pending.assign(c.n_layers, -1);
+  ctx->seq.assign(c.n_layers, 0);
   for (int l = 0; l < c.n_layers; ++l) {
     hipEvent_t e = nullptr;
     if (hipEventCreateWithFlags(&e, kOrderingEvent) != hipSuccess) {
@@ -668,6 +674,7 @@ static int step_layers(xsv_ctx* ctx, int layer0, int n_layers, const xsv_tensor*
   }
   if (fork && ctx->overlap == 2) {
     if (hipEventRecord(ctx->ev_chain[layer0], ctx->side) != hipSuccess) return hip_fail(ctx);
+    ctx->seq[layer0] = ctx->next_seq++;
     for (int l = layer0; l < layer0 + n_layers; ++l) ctx->pending[l] = layer0;
   } else if (fork) {  // join even after an error so the streams stay ordered
     if (hipEventRecord(ctx->ev_join, ctx->side) != hipSuccess || hipStreamWaitEvent(ctx->stream, ctx->ev_join, 0) != hipSuccess)
