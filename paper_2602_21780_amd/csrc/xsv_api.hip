@@ -131,6 +131,16 @@ int join_layers(xsv_ctx* ctx, int l0, int n) {
   return XSV_OK;
 }
 
+// For the synchronous introspection calls: the side stream's work on the layer is ordered into the context's
+// stream AND waited for from the host, so that copies to the host made next see it whatever fence the ordering
+// events carry.
+int settle_layer(xsv_ctx* ctx, int layer) {
+  const int rc = join_layers(ctx, layer, 1);
+  if (rc != XSV_OK) return rc;
+  if (ctx->side && hipStreamSynchronize(ctx->side) != hipSuccess) return hip_fail(ctx);
+  return XSV_OK;
+}
+
 // What a step does to the cache length (paper Sec. 3.2: prune once T exceeds the budget; first and
 // current frames always stay).  Pure token counting — known on the host without reading the GPU.
 struct PrunePlan {
@@ -733,7 +743,7 @@ int xsv_cache_export(xsv_ctx* ctx, int layer, uint8_t* k_codes, float* k_scale, 
   if (rc != XSV_OK) return rc;
   const LayerState& L = ctx->layers[layer];
   if (L.phase != kIdle) return XSV_ERR_STATE;
-  if ((rc = join_layers(ctx, layer, 1)) != XSV_OK) return rc;
+  if ((rc = settle_layer(ctx, layer)) != XSV_OK) return rc;
   const xsv_config& c = ctx->cfg;
   const bool quant = c.kv_bits != 16;
   if (!quant && (k_codes || k_scale || k_zero || v_codes || v_scale || v_zero)) return XSV_ERR_ARG;
@@ -791,7 +801,7 @@ int xsv_cache_import(xsv_ctx* ctx, int layer, int32_t T, int32_t frames_seen, co
   }
   const int H = c.n_heads, G = c.group_size, bits = c.kv_bits;
   const LayerCache lc = layer_cache(p, L.buf, layer);
-  if ((rc = join_layers(ctx, layer, 1)) != XSV_OK) return rc;
+  if ((rc = settle_layer(ctx, layer)) != XSV_OK) return rc;
   if (hipStreamSynchronize(ctx->stream) != hipSuccess) return hip_fail(ctx);
   // pack on the host into the library's private layout (layout marshalling only)
   const size_t row_bytes = p.code_row_bytes();
@@ -847,7 +857,7 @@ int xsv_last_selection(xsv_ctx* ctx, int layer, int32_t* n_scores, float* scores
   int rc = check_layer(ctx, layer);
   if (rc != XSV_OK) return rc;
   const LayerState& L = ctx->layers[layer];
-  if ((rc = join_layers(ctx, layer, 1)) != XSV_OK) return rc;
+  if ((rc = settle_layer(ctx, layer)) != XSV_OK) return rc;
   if (n_scores) *n_scores = L.last_P;
   if (n_keep) *n_keep = L.last_keep;
   bool good = true;
