@@ -98,14 +98,15 @@ int xsv_frame_attend(xsv_ctx* ctx, xsv_tensor q, xsv_tensor k, xsv_tensor v, voi
  *   consecutive groups of pool_size (a short last group over its real size)],
  *   Kbar = head-mean of the dequantized cached keys of the middle,
  * and the keep list is first frame ∪ top-k middle (equal scores: smaller position first) ∪ current
- * frame, in ascending position.  One list per layer, shared by all heads and by K and V.
- * Writes context-owned scores and keep list; frame-t keys themselves are never scored. */
+ * frame, in ascending position.  One list per layer, shared by all heads and by K and V (score_mode 1:
+ * the head-means are left out, head h scores its own keys with its own pooled queries, and there is one
+ * list per head).  Writes context-owned scores and keep list(s); frame-t keys themselves are never scored. */
 int xsv_score_prune(xsv_ctx* ctx, int layer, xsv_tensor q);
 
 /* Sec. 3.3 on the final cache of the step: gathers the kept rows (cached rows through their
  * dequantized bf16 view (code - zero) * scale, frame rows as given) and quantizes all of them:
  *   s = (max - min) / (2^b - 1)  (s = 1 if max == min),  zero = round(-min / s),
- *   code = clamp(round(x / s) + zero, 0, 2^b - 1),   round = nearest-even, fp32 IEEE division,
+ *   code = clamp(round(x / s) + zero, 0, 2^b - 1),   round = nearest-even, x / s the IEEE fp32 quotient,
  * keys per (head, channel) over groups of G consecutive kept tokens (short last group on its own),
  * values per (head, token) over groups of G consecutive channels.  With kv_bits == 16 the rows are
  * stored as bf16 unchanged.  Swaps the layer's cache buffers; cache length becomes the keep length. */
@@ -150,7 +151,7 @@ int xsv_join(xsv_ctx* ctx);
  * is long (more than about 24 key tiles per workgroup).  Ignored when overlap is off or splits are fixed. */
 int xsv_set_side_cus(xsv_ctx* ctx, int compute_units);
 /* Tuning: in xsv_step / xsv_step_all_layers with overlap, cut every (head, query block) into one more key
- * range than the spare units allow, the extra one `percent` of a full range long (1..100; 0 = off): its
+ * range than the spare units allow, the extra one `percent` of a full range long (1..100, default 35; 0 = off): its
  * workgroups end early and hand their compute units to the chain for the rest of the attention launch. */
 int xsv_set_short_range(xsv_ctx* ctx, int percent);
 /* Measurement aid.  While enabled, every attention launch of this context (xsv_dequant_attend, xsv_step,
