@@ -71,3 +71,23 @@ def test_null_context_is_rejected(lib):
     assert lib.xsv_attend_times(None, None, None, None, None) == xsv.XSV_ERR_ARG
     assert lib.xsv_chain_times(None, None, None, None) == xsv.XSV_ERR_ARG
     assert lib.xsv_last_attend_workgroups(None, None) == xsv.XSV_ERR_ARG
+
+
+def test_header_compiles_as_c_and_every_entry_point_links(tmp_path):
+    """A C99 program against include/xsv.h and libxsv.so (no GPU needed for what it calls)."""
+    import os
+    import shutil
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    cc = shutil.which("gcc") or shutil.which("cc")
+    if cc is None:
+        pytest.skip("no C compiler")
+    exe = str(tmp_path / "abi_check")
+    libdir = os.path.join(root, "paper_2602_21780_amd")
+    cmd = [cc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(root, "include"),
+           os.path.join(root, "tests", "c", "abi_check.c"), "-o", exe, "-L", libdir, "-lxsv", "-Wl,-rpath," + libdir,
+           "-Wl,-rpath-link,/opt/rocm/lib"]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    r = subprocess.run([exe], capture_output=True, text=True)
+    assert r.returncode == 0 and "abi ok" in r.stdout, (r.returncode, r.stdout, r.stderr)
