@@ -246,6 +246,26 @@ def test_free_running_overlapped_stream_equals_one_stream_at_full_size():
         assert np.array_equal(x, y)
 
 
+def test_contexts_give_their_memory_back():
+    """Create, step, export, destroy - sixty times; the device's free memory ends where it started."""
+    spec = CONFIGS[0].with_(name="cycle", n_layers=3, n_heads=4, tokens_per_frame=150, budget=400, group_size=64)
+    q, k, v = FrameSource(spec, DEV).frame(0)
+    torch.cuda.synchronize()
+    free0, _ = torch.cuda.mem_get_info()
+    for i in range(60):
+        ctx = xsv.Context.from_spec(spec, score_mode=i % 2)
+        ctx.set_overlap(i % 3)
+        ctx.set_attend_timing(i % 4 == 0)
+        for l in range(spec.n_layers):
+            ctx.step(l, q[l], k[l], v[l])
+        ctx.join()
+        ctx.cache_export(1)
+        ctx.destroy()
+    torch.cuda.synchronize()
+    free1, _ = torch.cuda.mem_get_info()
+    assert abs(free0 - free1) < (64 << 20), (free0, free1)
+
+
 def test_same_inputs_twice_give_identical_bytes():
     spec = CONFIGS[0].with_(name="determinism", n_heads=4, tokens_per_frame=150, budget=400, group_size=64)
     dumps = []
