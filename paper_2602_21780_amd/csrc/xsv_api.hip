@@ -118,13 +118,21 @@ void free_all(xsv_ctx* ctx) {
 
 // Orders the context's stream after the side-stream work still outstanding for layers [l0, l0 + n): ONE wait, for
 // the latest of their records (the side stream runs in order), which also settles every layer recorded before it.
-int join_layers(xsv_ctx* ctx, int l0, int n) {
+// A wait costs the waiting stream several microseconds even when the event has long fired, so a step that has to
+// wait anyway waits for a NEWER record if there is one that is `settled_lag` records old or older - the chains
+// behind such a record have had time to finish - and thereby settles the layers the following steps would each
+// have waited for (one wait per frame instead of one per layer when the caller never calls xsv_join).
+int join_layers(xsv_ctx* ctx, int l0, int n, int settled_lag = -1) {
   int latest = -1;
   for (int l = l0; l < l0 + n; ++l) {
     const int e = ctx->pending[l];
     if (e >= 0 && (latest < 0 || ctx->seq[e] > ctx->seq[latest])) latest = e;
   }
   if (latest < 0) return XSV_OK;
+  if (settled_lag >= 0) {
+    for (int e : ctx->pending)
+      if (e >= 0 && ctx->seq[e] > ctx->seq[latest] && ctx->seq[e] <= ctx->next_seq - 1 - settled_lag) latest = e;
+  }
   if (hipStreamWaitEvent(ctx->stream, ctx->ev_chain[latest], 0) != hipSuccess) return hip_fail(ctx);
   for (int& e : ctx->pending)
     if (e >= 0 && ctx->seq[e] <= ctx->seq[latest]) e = -1;
@@ -628,7 +636,7 @@ int xsv_quantize(xsv_ctx* ctx, int layer, xsv_tensor k_new, xsv_tensor v_new) {
 static int step_layers(xsv_ctx* ctx, int layer0, int n_layers, const xsv_tensor* q, const xsv_tensor* k,
                        const xsv_tensor* v, void* const* out, int splits) {
   const bool fork = ctx->overlap != 0;
-  int rc = join_layers(ctx, layer0, n_layers);  // the previous frame's chain wrote the cache read now
+  int rc = join_layers(ctx, layer0, n_layers, 2);  // the previous frame's chain wrote the cache read now
   if (rc != XSV_OK) return rc;
   if (fork) {
     if (hipEventRecord(ctx->ev_fork, ctx->stream) != hipSuccess || hipStreamWaitEvent(ctx->side, ctx->ev_fork, 0) != hipSuccess)
