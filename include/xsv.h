@@ -126,10 +126,6 @@ int xsv_step(xsv_ctx* ctx, int layer, xsv_tensor q, xsv_tensor k_new, xsv_tensor
 int xsv_step_all_layers(xsv_ctx* ctx, const xsv_tensor* q, const xsv_tensor* k_new, const xsv_tensor* v_new,
                         void* const* out);
 
-/* Tuning: number of equal key ranges every (head, block of query rows) is cut into by the attention
- * kernel (partial results are merged by a second kernel), 1..16.  0 (default) = one workgroup per
- * slot of the chip, the key tiles of all (head, query block) pairs dealt out evenly among them. */
-int xsv_set_attend_splits(xsv_ctx* ctx, int per_layer_calls, int batched_calls);
 /* How xsv_step / xsv_step_all_layers order the score/select/re-quantize chain:
  *   0  everything on the context's stream, in order;
  *   1  (default) the chain overlaps the attention kernel on the context's side stream and the
@@ -145,37 +141,6 @@ int xsv_set_overlap(xsv_ctx* ctx, int mode);
 /* Orders the context's stream after all side-stream work enqueued so far (no host wait).  A no-op
  * unless overlap mode 2 has steps outstanding. */
 int xsv_join(xsv_ctx* ctx);
-/* Tuning: compute units the attention launch of xsv_step / xsv_step_all_layers leaves free for the
- * overlapped score/select/re-quantize chain (0 .. half the chip).  Without spare units the chain only
- * starts when attention drains.  -1 (default) = a quarter of the chip, an eighth when the attention launch
- * is long (more than about 24 key tiles per workgroup).  Ignored when overlap is off or splits are fixed. */
-int xsv_set_side_cus(xsv_ctx* ctx, int compute_units);
-/* Tuning: in xsv_step / xsv_step_all_layers with overlap, cut every (head, query block) into one more key
- * range than the spare units allow, the extra one `percent` of a full range long (1..100, default 35; 0 = off): its
- * workgroups end early and hand their compute units to the chain for the rest of the attention launch. */
-int xsv_set_short_range(xsv_ctx* ctx, int percent);
-/* Measurement aid.  While enabled, every attention launch of this context (xsv_dequant_attend, xsv_step,
- * xsv_step_all_layers) is bracketed by events on the context's stream: before the attention kernel,
- * between it and the kernel that merges key-range partials, after, and once more right behind.
- * xsv_attend_times waits for the stream, returns the number of launches recorded since the last call (or
- * since enabling), the average span of each of the two kernels in milliseconds and (event_ms, may be NULL)
- * the average span of the last two events, which have nothing between them: what an event pair itself adds
- * to a span.  It then starts a new series.  Enabling or disabling discards the series.  The events cost a
- * few microseconds per launch; leave this off in production. */
-int xsv_set_attend_timing(xsv_ctx* ctx, int enabled);
-int xsv_attend_times(xsv_ctx* ctx, int32_t* launches, float* attend_ms, float* merge_ms, float* event_ms);
-/* With the same switch, xsv_step and xsv_step_all_layers also bracket their score + select launches and
- * their re-quantize launch with events on the stream those run on.  Returns the number of steps recorded,
- * the average span of the two stages in milliseconds (event cost included), and starts a new series.  In the
- * overlapped modes the spans include whatever the attention running beside them takes away. */
-int xsv_chain_times(xsv_ctx* ctx, int32_t* steps, float* score_prune_ms, float* quantize_ms);
-/* Grid (workgroups) of the most recent attention launch of this context, 0 before the first. */
-int xsv_last_attend_workgroups(xsv_ctx* ctx, int32_t* workgroups);
-/* Tuning: workgroup shape of the attention kernel (waves x query rows per wave).  3 = 8 x 64, 0 = 4 x 64,
- * 1 = 4 x 32, 2 = 8 x 32.  Default: 3, or 2 where blocks of 256 rows pad a frame's tokens less than blocks
- * of 512 (e.g. 1041 tokens).  Other values: XSV_ERR_ARG.  Results agree to rounding. */
-int xsv_set_attend_variant(xsv_ctx* ctx, int variant);
-
 /* ---- introspection, synchronous, HOST buffers, canonical unpacked layout ------------------------ */
 
 /* Cache length T of a layer (tokens per head). */
@@ -221,11 +186,6 @@ int xsv_score(void* hip_stream, xsv_tensor q, const void* k_mid_bf16, int H, int
 /* Sec. 3.2 keep list from scores [P]: [0,T_first) ∪ (T_first + top-k) ∪ [T_first+P, T_first+P+T_cur),
  * ascending; keep: int32 [T_first + k + T_cur]. */
 int xsv_topk_keep(void* hip_stream, const float* scores, int P, int k, int T_first, int T_cur, int32_t* keep);
-
-/* Measurement aid, synchronous: two yardsticks of the current device - the rate of a loop of nothing but the bf16
- * MFMA instruction the attention kernel uses (TFLOP/s, all compute units busy) and of a plain streaming copy of
- * 512 MiB (GB/s, bytes read + bytes written).  Allocates and frees 1 GiB of temporaries; takes about 50 ms. */
-int xsv_measure_peaks(void* hip_stream, float* mfma_bf16_tflops, float* copy_gbs);
 
 const char* xsv_strerror(int code);
 

@@ -2,7 +2,7 @@
 // v_mfma_f32_32x32x16_bf16 (the instruction the attention kernel computes with) and the rate of a plain
 // streaming copy.  The published peaks (2.5 PFLOP/s dense bf16, 8 TB/s) are what the benchmark's
 // roofline is priced against; these say how much of them any kernel can reach on this chip and clock.
-#include "../../include/xsv.h"
+#include "../../include/xsv_tune.h"
 #include "xsv_internal.h"
 
 namespace xsv {

@@ -3,6 +3,7 @@
 // file only decides WHICH launches a step needs (the cache lengths are known on the host: they
 // depend on token counts alone) and owns the device memory.
 #include "../../include/xsv.h"
+#include "../../include/xsv_tune.h"
 
 #include <algorithm>
 #include <cmath>
@@ -114,6 +115,18 @@ void free_all(xsv_ctx* ctx) {
   ctx->ev_chain.clear();
   ctx->side = nullptr;
   ctx->ev_fork = ctx->ev_join = nullptr;
+}
+
+// An event that only orders streams.  A runtime that does not know the no-system-fence flag gets a plain
+// untimed event (same ordering, a little more cost per record).
+bool ordering_event(hipEvent_t* e) {
+  if (hipEventCreateWithFlags(e, kOrderingEvent) == hipSuccess) return true;
+  (void)hipGetLastError();
+  *e = nullptr;
+  if (hipEventCreateWithFlags(e, hipEventDisableTiming) == hipSuccess) return true;
+  (void)hipGetLastError();
+  *e = nullptr;
+  return false;
 }
 
 // Orders the context's stream after the side-stream work still outstanding for layers [l0, l0 + n): ONE wait, for
@@ -414,12 +427,17 @@ int xsv_create(const xsv_config* cfg, void* hip_stream, xsv_ctx** out) {
   ctx->stream = static_cast<hipStream_t>(hip_stream);
   ctx->work = ctx->stream;
   ctx->layers.resize(c.n_layers);
-  if (hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) != hipSuccess ||
-      hipEventCreateWithFlags(&ctx->ev_fork, kOrderingEvent) != hipSuccess ||
-      hipEventCreateWithFlags(&ctx->ev_join, kOrderingEvent) != hipSuccess) {
-    if (ctx->side) (void)hipStreamDestroy(ctx->side);
-    if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
-    if (ctx->ev_join) (void)hipEventDestroy(ctx->ev_join);
+  // the device is queried before anything is created, so this failure has nothing to release
+  int dev = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) {
+    (void)hipGetLastError();
+    delete ctx;
+    return XSV_ERR_HIP;
+  }
+  if (hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) != hipSuccess || !ordering_event(&ctx->ev_fork) ||
+      !ordering_event(&ctx->ev_join)) {
+    free_all(ctx);
     delete ctx;
     return XSV_ERR_HIP;
   }
@@ -430,18 +448,12 @@ int xsv_create(const xsv_config* cfg, void* hip_stream, xsv_ctx** out) {
   ctx->seq.assign(c.n_layers, 0);
   for (int l = 0; l < c.n_layers; ++l) {
     hipEvent_t e = nullptr;
-    if (hipEventCreateWithFlags(&e, kOrderingEvent) != hipSuccess) {
+    if (!ordering_event(&e)) {
       free_all(ctx);
       delete ctx;
       return XSV_ERR_HIP;
     }
     ctx->ev_chain.push_back(e);
-  }
-  int dev = 0;
-  hipDeviceProp_t prop;
-  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) {
-    delete ctx;
-    return XSV_ERR_HIP;
   }
   ctx->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
 
@@ -636,6 +648,11 @@ int xsv_quantize(xsv_ctx* ctx, int layer, xsv_tensor k_new, xsv_tensor v_new) {
 static int step_layers(xsv_ctx* ctx, int layer0, int n_layers, const xsv_tensor* q, const xsv_tensor* k,
                        const xsv_tensor* v, void* const* out, int splits) {
   const bool fork = ctx->overlap != 0;
+  {  // every tensor of the batch is checked before the first launch (the stages check again as they marshal)
+    Batch probe;
+    const int bad = fill_batch(ctx, probe, layer0, n_layers, q, k, v, out);
+    if (bad != XSV_OK) return bad;
+  }
   int rc = join_layers(ctx, layer0, n_layers, 2);  // the previous frame's chain wrote the cache read now
   if (rc != XSV_OK) return rc;
   if (fork) {

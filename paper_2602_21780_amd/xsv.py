@@ -42,9 +42,14 @@ class xsv_tensor(C.Structure):
 # every symbol include/xsv.h declares
 EXPORTS = (
     "xsv_create", "xsv_destroy", "xsv_reset", "xsv_dequant_attend", "xsv_frame_attend", "xsv_score_prune", "xsv_quantize",
-    "xsv_step", "xsv_step_all_layers", "xsv_set_attend_splits", "xsv_set_attend_variant", "xsv_set_overlap", "xsv_join", "xsv_set_side_cus", "xsv_set_short_range", "xsv_last_attend_workgroups", "xsv_set_attend_timing", "xsv_attend_times", "xsv_chain_times", "xsv_cache_len", "xsv_cache_export",
+    "xsv_step", "xsv_step_all_layers", "xsv_set_overlap", "xsv_join", "xsv_cache_len", "xsv_cache_export",
     "xsv_cache_import", "xsv_last_selection", "xsv_quantize_k", "xsv_quantize_v", "xsv_score",
-    "xsv_topk_keep", "xsv_measure_peaks", "xsv_strerror",
+    "xsv_topk_keep", "xsv_strerror",
+)
+# every symbol include/xsv_tune.h declares (launch tuning and measurement aids)
+TUNE_EXPORTS = (
+    "xsv_set_attend_splits", "xsv_set_attend_variant", "xsv_set_side_cus", "xsv_set_short_range",
+    "xsv_last_attend_workgroups", "xsv_set_attend_timing", "xsv_attend_times", "xsv_chain_times", "xsv_measure_peaks",
 )
 
 _lib = None
@@ -90,7 +95,7 @@ def lib():
         L.xsv_measure_peaks.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_float)]
         L.xsv_strerror.argtypes = [i32]
         L.xsv_strerror.restype = C.c_char_p
-        for name in EXPORTS:
+        for name in EXPORTS + TUNE_EXPORTS:
             if name != "xsv_strerror":
                 getattr(L, name).restype = C.c_int
         _lib = L

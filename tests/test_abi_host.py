@@ -20,11 +20,12 @@ def lib():
 
 
 def test_every_declared_symbol_is_exported(lib):
-    header = open(os.path.join(ROOT, "include", "xsv.h")).read()
-    declared = set(re.findall(r"\b(xsv_[a-z_]+)\s*\(", header))
-    assert declared == set(xsv.EXPORTS)
-    for name in declared:
-        assert hasattr(lib, name), name
+    for header_name, exports in (("xsv.h", xsv.EXPORTS), ("xsv_tune.h", xsv.TUNE_EXPORTS)):
+        header = open(os.path.join(ROOT, "include", header_name)).read()
+        declared = set(re.findall(r"\b(xsv_[a-z_]+)\s*\(", header))
+        assert declared == set(exports), header_name
+        for name in declared:
+            assert hasattr(lib, name), name
 
 
 def test_strerror(lib):

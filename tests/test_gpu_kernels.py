@@ -98,7 +98,8 @@ def test_quantize_extreme_magnitudes_next_to_ordinary_groups(bits):
             assert np.array_equal(codes.cpu().numpy(), rc)
 
 
-@pytest.mark.parametrize("H,n,n_s,P,g", [(2, 64, 5, 192, 16), (16, 1374, 5, 2722, 16), (3, 37, 5, 70, 4), (1, 21, 0, 1, 1)])
+@pytest.mark.parametrize("H,n,n_s,P,g", [(2, 64, 5, 192, 16), (16, 1374, 5, 2722, 16), (3, 37, 5, 70, 4), (1, 21, 0, 1, 1),
+                                         (20, 150, 5, 333, 16), (37, 90, 3, 100, 7)])
 def test_score_matches_oracle(H, n, n_s, P, g):
     print(f"score H={H} n={n} P={P}", flush=True)
     q = randn_bf16((H, n, 64), n + P)

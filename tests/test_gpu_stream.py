@@ -12,7 +12,16 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-def run_stream(spec, frames, rows=None, splits=0, short=None, **over):
+def cover_rows(n):
+    """Sampled query rows that reach every 32-row block of the frame - so every wave of every attention
+    workgroup, and both query blocks of a wave, whatever the workgroup shape - plus the special tokens, the
+    first patch row and the last row."""
+    blocks = [min(b + (7 * (b // 32) + 3) % 32, n - 1) for b in range(0, n, 32)]
+    return np.unique(np.array([0, min(4, n - 1), min(5, n - 1), n - 1] + blocks, np.int32))
+
+
+def run_stream(spec, frames, rows=None, splits=0, short=None, all_rows_from=None, **over):
+    """`rows`: the query rows whose attention is compared (None = all); from frame `all_rows_from` on, all."""
     ctx, st = parity.make_pair(spec, **over)
     if splits:
         ctx.set_attend_splits(splits, splits)
@@ -25,7 +34,8 @@ def run_stream(spec, frames, rows=None, splits=0, short=None, **over):
         q, k, v = src.frame(f)
         for l in range(spec.n_layers):
             print(f"  {spec.name} frame {f} layer {l} T={ctx.cache_len(l)}", flush=True)
-            (ma, rr), t = parity.step_and_compare(ctx, st, spec, l, l, q[l], k[l], v[l], rows=rows,
+            full = all_rows_from is not None and f >= all_rows_from
+            (ma, rr), t = parity.step_and_compare(ctx, st, spec, l, l, q[l], k[l], v[l], rows=None if full else rows,
                                                   budget=over.get("budget"))
             worst = (max(worst[0], ma), max(worst[1], rr))
             ties += t
@@ -85,6 +95,15 @@ def test_per_head_selection(bits, G, H):
     run_stream(spec, 7, score_mode=1)
 
 
+@pytest.mark.parametrize("bits,G", [(4, 64), (2, 32)])
+def test_more_heads_than_one_score_chunk_in_the_papers_mode(bits, G):
+    """20 heads with the head-averaged score (Sec. 3.2): the score kernel walks the heads in chunks of 16 and
+    carries the head sums from one chunk to the next; quantized cache."""
+    spec = CONFIGS[0].with_(name=f"h20-b{bits}-g{G}", n_heads=20, tokens_per_frame=150, budget=520, kv_bits=bits,
+                            group_size=G, n_layers=1, seed=29)
+    run_stream(spec, 7)
+
+
 def test_per_head_selection_batched_equals_per_layer_steps():
     spec = CONFIGS[0].with_(name="perhead-batched", n_layers=3, n_heads=4, tokens_per_frame=150, budget=400, group_size=64, seed=19)
     ctx_a = xsv.Context.from_spec(spec, score_mode=1)
@@ -114,11 +133,11 @@ def test_every_workgroup_shape_of_the_attention_kernel(variant, splits):
     ctx.set_attend_variant(variant)
     ctx.set_attend_splits(splits, splits)
     src = FrameSource(spec, DEV)
-    rows = np.array([0, 31, 32, 63, 64, 255, 256, 300, 511, 512, 575, 576, 599], np.int32)
+    rows = np.unique(np.concatenate([cover_rows(600), np.array([31, 32, 63, 64, 255, 256, 511, 512, 575, 576], np.int32)]))
     for f in range(5):
         q, k, v = src.frame(f)
         print(f"  {spec.name} frame {f} T={ctx.cache_len(0)}", flush=True)
-        parity.step_and_compare(ctx, st, spec, 0, 0, q[0], k[0], v[0], rows=rows)
+        parity.step_and_compare(ctx, st, spec, 0, 0, q[0], k[0], v[0], rows=None if f == 4 else rows)
     ctx.destroy()
 
 
@@ -360,53 +379,79 @@ def test_bad_arguments_are_rejected_before_anything_is_launched():
     ctx.destroy()
 
 
-def test_one_layer_config_full_size_sampled_rows():
-    """cfg 1 at its real shape (16 heads, 1374 tokens, budget 2048 < first + current, so k = 0):
-    cache bytes compared in full, attention on sampled query rows incl. the ragged last tile."""
+def test_batched_call_with_mismatched_strides_launches_nothing():
+    """xsv_step_all_layers with one layer's K on other strides than the rest: an argument error before any
+    launch - no layer changes phase, and the stream goes on afterwards."""
+    spec = CONFIGS[0].with_(name="strides", n_layers=3, n_heads=2, tokens_per_frame=100, budget=300, group_size=64)
+    ctx = xsv.Context.from_spec(spec)
+    lib = xsv.lib()
+    src = FrameSource(spec, DEV)
+    q, k, v = src.frame(0)
+    out = ctx.step_all_layers(q, k, v)
+    q, k, v = src.frame(1)
+    wide = torch.zeros((spec.n_heads, spec.tokens_per_frame, 128), dtype=torch.bfloat16, device=DEV)
+    wide[:, :, :64] = k[1]
+    k_odd = [k[0], wide[:, :, :64], k[2]]
+    for which in ("k", "v", "q"):
+        args = {"q": q, "k": k, "v": v}
+        args[which] = k_odd if which == "k" else [args[which][0], wide[:, :, :64], args[which][2]]
+        packed = ctx.pack_layers(args["q"], args["k"], args["v"], out)
+        assert lib.xsv_step_all_layers(ctx._h, *packed) == xsv.XSV_ERR_ARG
+    for l in range(spec.n_layers):
+        assert ctx.cache_len(l) == spec.tokens_per_frame
+    ctx.step_all_layers(q, k, v, out)                  # every layer is still idle: the frame steps normally
+    torch.cuda.synchronize()
+    for l in range(spec.n_layers):
+        assert ctx.cache_len(l) == 2 * spec.tokens_per_frame
+        ctx.step(l, q[l], k[l], v[l])
+    ctx.destroy()
+
+
+def test_one_layer_config_full_size():
+    """cfg 1 at its real shape (16 heads, 1374 tokens, budget 2048 < first + current, so k = 0): cache bytes
+    compared in full every frame; attention on rows that reach every wave of every workgroup, and on ALL rows
+    once the cache has reached its steady length (frames 4 and 5: 2748 cached tokens, 4122 keys)."""
     spec = CONFIGS[1]
-    rows = np.array([0, 4, 5, 31, 32, 700, 1343, 1344, 1372, 1373], np.int32)
-    run_stream(spec, 4, rows=rows)
+    run_stream(spec, 6, rows=cover_rows(spec.tokens_per_frame), all_rows_from=4)
 
 
-def test_24_layer_config_shape_two_layers_sampled_rows():
-    """cfg 2 shape (budget 4096, top-k of 1348 from 2722 once saturated) on two of its layers."""
+def test_24_layer_config_shape_two_layers():
+    """cfg 2 shape (budget 4096, top-k of 1348 from 2722 once saturated) on two of its layers; all query rows
+    at the saturated cache (frame 5: 4096 cached tokens, 5470 keys)."""
     spec = CONFIGS[2].with_(n_layers=2)
-    rows = np.array([0, 3, 64, 777, 1311, 1373], np.int32)
-    run_stream(spec, 6, rows=rows)
+    run_stream(spec, 6, rows=cover_rows(spec.tokens_per_frame), all_rows_from=5)
 
 
-def test_24_layer_config_shape_per_head_selection_sampled_rows():
+def test_24_layer_config_shape_per_head_selection():
     """cfg 2 shape with every head keeping its own top 1348 of 2722 (score_mode 1), two layers."""
     spec = CONFIGS[2].with_(n_layers=2)
-    rows = np.array([0, 3, 64, 777, 1311, 1373], np.int32)
-    run_stream(spec, 6, rows=rows, score_mode=1)
+    run_stream(spec, 6, rows=cover_rows(spec.tokens_per_frame), all_rows_from=5, score_mode=1)
 
 
-def test_2bit_config_shape_sampled_rows():
-    """cfg 4 shape (1041 tokens, 2-bit, budget 8192) on one layer until the first prune."""
+def test_2bit_config_shape_one_layer():
+    """cfg 4 shape (1041 tokens, 2-bit, budget 8192) on one layer past the first two prunes (frame 8: 7287
+    cached, k = 6110 of 6246; frame 9: the saturated 8192, k = 6110 of 7151); all query rows on those two."""
     spec = CONFIGS[4].with_(n_layers=1)
-    rows = np.array([0, 5, 1000, 1040], np.int32)
-    run_stream(spec, 9, rows=rows)
+    run_stream(spec, 10, rows=cover_rows(spec.tokens_per_frame), all_rows_from=8)
 
 
-def test_24_layer_config_as_benchmarked_three_layers_checked():
-    """cfg 2 with all 24 layers in the launch configuration bench.py times (overlap mode 2, one join per
-    frame, default attention grid); the oracle follows layers 0, 11 and 23 (cache bytes in full, attention
-    on sampled rows), the other layers only run."""
-    spec = CONFIGS[2]
-    checked = [0, 11, 23]
+def _stack_as_benchmarked(spec, checked, n_frames, full_from):
+    """All layers of `spec` in the launch configuration bench.py times (overlap mode 2, one join per frame,
+    default attention grid); the oracle follows the `checked` layers (cache bytes in full, attention on rows
+    that reach every wave, ALL rows from frame `full_from` on), the other layers only run."""
     ctx, st = parity.make_pair(spec, layers=checked)
     ctx.set_overlap(2)
     src = FrameSource(spec, DEV)
-    rows = np.array([0, 4, 5, 511, 512, 1023, 1024, 1373], np.int32)
-    frames = [src.frame(f) for f in range(6)]          # kept alive, as overlap mode 2 requires
+    rows = cover_rows(spec.tokens_per_frame)
+    frames = [src.frame(f) for f in range(n_frames)]          # kept alive, as overlap mode 2 requires
     out = torch.empty((spec.n_layers, spec.n_heads, spec.tokens_per_frame, spec.head_dim), dtype=torch.bfloat16, device=DEV)
     worst, ties = (0.0, 0.0), 0
     for f, (q, k, v) in enumerate(frames):
         for l in range(spec.n_layers):
             if l in checked:
                 print(f"  {spec.name} frame {f} layer {l} T={ctx.cache_len(l)}", flush=True)
-                (ma, rr), t = parity.step_and_compare(ctx, st, spec, l, checked.index(l), q[l], k[l], v[l], rows=rows)
+                (ma, rr), t = parity.step_and_compare(ctx, st, spec, l, checked.index(l), q[l], k[l], v[l],
+                                                      rows=None if f >= full_from else rows)
                 worst, ties = (max(worst[0], ma), max(worst[1], rr)), ties + t
             else:
                 ctx.step(l, q[l], k[l], v[l], out[l])
@@ -419,22 +464,37 @@ def test_24_layer_config_as_benchmarked_three_layers_checked():
     ctx.destroy()
 
 
-def test_long_drifting_stream_one_layer_300_frames():
-    """One layer of the long-horizon workload for 300 frames: keep lists and scores every frame, attention on
-    sampled rows every frame, the whole cache every tenth frame (about 15 s, most of it the oracle).  By hand the
-    same loop was run for the workload's full 1000 frames: all checks passed, with one documented near-tie."""
+def test_24_layer_config_as_benchmarked_three_layers_checked():
+    """cfg 2, all 24 layers as bench.py runs them; layers 0, 11 and 23 against the oracle, every query row on
+    the saturated frames 5 and 6."""
+    _stack_as_benchmarked(CONFIGS[2], [0, 11, 23], 7, 5)
+
+
+def test_2bit_24_layer_config_as_benchmarked_three_layers_checked():
+    """cfg 4 (24 layers, 1041 tokens, 2-bit, budget 8192), all layers in the benchmarked launch form; layers
+    0, 12 and 23 against the oracle, every query row on the saturated frame 9."""
+    _stack_as_benchmarked(CONFIGS[4], [0, 12, 23], 10, 9)
+
+
+@pytest.mark.timeout(900)
+def test_long_drifting_stream_one_layer_1000_frames():
+    """One layer of the long-horizon workload for all of its 1000 frames: keep lists and scores every frame,
+    attention on sampled rows every frame (rows reaching every wave every 25th frame, all rows on the last),
+    the whole cache every tenth frame.  Most of the time is the oracle's."""
     spec = CONFIGS[3].with_(n_layers=1)
-    rows = np.array([0, 5, 700, 1373], np.int32)
+    few = np.array([0, 5, 700, 1373], np.int32)
+    cover = cover_rows(spec.tokens_per_frame)
     ctx, st = parity.make_pair(spec)
     src = FrameSource(spec, DEV, layers=[0])
     worst, ties = (0.0, 0.0), 0
-    for f in range(300):
+    for f in range(spec.frames):
         q, k, v = src.frame(f)
+        rows = None if f == spec.frames - 1 else (cover if f % 25 == 24 else few)
         (ma, rr), t = parity.step_and_compare(ctx, st, spec, 0, 0, q[0], k[0], v[0], rows=rows, check_cache=f % 10 == 9)
         worst, ties = (max(worst[0], ma), max(worst[1], rr)), ties + t
         if f % 50 == 49:
             print(f"  frame {f + 1}: worst max_abs={worst[0]:.3e} rel_rms={worst[1]:.3e} ties={ties}", flush=True)
-    assert ctx.cache_len(0) == spec.budget
+    assert spec.frames == 1000 and ctx.cache_len(0) == spec.budget
     ctx.destroy()
 
 
