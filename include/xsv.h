@@ -183,6 +183,17 @@ int xsv_quantize_v(void* hip_stream, const void* v_bf16, int H, int T, int d, in
  * (n rows, first n_s special, pooling size g).  scores: float [P]. */
 int xsv_score(void* hip_stream, xsv_tensor q, const void* k_mid_bf16, int H, int n, int n_s, int P, int d, int g,
               float* scores);
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc): xsv_score with its one temporary - the per-head partial sums of the pooled query - in
+ * a fixed device array of the library instead of a hipMalloc'ed buffer.  Same arguments, same kernels, same
+ * scores as xsv_score.  Differences: it calls no hipMalloc / hipFree and does not wait - it only enqueues on
+ * hip_stream, so `scores` is valid once the stream has passed the call; H is limited to
+ * XSV_NOALLOC_MAX_HEADS (more: XSV_ERR_UNSUPPORTED, nothing launched); the array (16 KB) stays allocated on
+ * every device the call ran on until the process ends.  All calls on one device share that array: calls
+ * whose kernels could overlap on one device (different streams, no ordering between them) race; order them. */
+#define XSV_NOALLOC_MAX_HEADS 64
+int xsv_score_noalloc(void* hip_stream, xsv_tensor q, const void* k_mid_bf16, int H, int n, int n_s, int P, int d, int g,
+                      float* scores);
 /* Sec. 3.2 keep list from scores [P]: [0,T_first) ∪ (T_first + top-k) ∪ [T_first+P, T_first+P+T_cur),
  * ascending; keep: int32 [T_first + k + T_cur]. */
 int xsv_topk_keep(void* hip_stream, const float* scores, int P, int k, int T_first, int T_cur, int32_t* keep);

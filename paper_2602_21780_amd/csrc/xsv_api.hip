@@ -8,6 +8,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <type_traits>
 #include <vector>
@@ -961,6 +962,61 @@ int xsv_score(void* hip_stream, xsv_tensor q, const void* k_mid_bf16, int H, int
   s.k_plain = static_cast<const uint16_t*>(k_mid_bf16);
   if (launch_pool_query(s, stream) != hipSuccess || launch_score(s, stream) != hipSuccess) return XSV_ERR_HIP;
   return hipStreamSynchronize(stream) == hipSuccess ? XSV_OK : XSV_ERR_HIP;
+}
+
+// ---- the entry point that allocates nothing ---------------------------------------------------------
+// xsv_score needs one scratch buffer: the per-head partial sums of the pooled query that pool_query_kernel
+// writes and score_kernel folds.  Here it lives in a file-scope device array instead of a hipMalloc'ed
+// temporary.  The array's name is only a host-side handle: its device address is looked up once per device
+// (each device holds its own copy) and that pointer is what the kernels get.
+constexpr int kNoAllocMaxHeads = XSV_NOALLOC_MAX_HEADS;
+constexpr int kNoAllocMaxDevices = 64;
+static __device__ __align__(256) float scratch[kNoAllocMaxHeads * kPoolSeg * kD];
+
+static std::mutex g_scratch_mutex;
+static float* g_scratch_ptr[kNoAllocMaxDevices];  // device address of `scratch` on device i, once resolved
+
+// The current device's copy of `scratch`; nullptr (and *rc set) on failure.
+static float* scratch_of_current_device(int* rc) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); *rc = XSV_ERR_HIP; return nullptr; }
+  if (dev < 0 || dev >= kNoAllocMaxDevices) { *rc = XSV_ERR_UNSUPPORTED; return nullptr; }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+      (void)hipGetLastError();
+      *rc = XSV_ERR_HIP;
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = static_cast<float*>(p);
+  }
+  return g_scratch_ptr[dev];
+}
+
+int xsv_score_noalloc(void* hip_stream, xsv_tensor q, const void* k_mid_bf16, int H, int n, int n_s, int P, int d, int g,
+                      float* scores) {
+  if (!tensor_ok(q) || !k_mid_bf16 || !scores || H < 1 || n < 1 || n_s < 0 || n_s > n || P < 1 || g < 1) return XSV_ERR_ARG;
+  if (d != kD) return XSV_ERR_UNSUPPORTED;
+  if (H > kNoAllocMaxHeads) return XSV_ERR_UNSUPPORTED;  // the scratch array holds kNoAllocMaxHeads partial sums
+  int rc = XSV_OK;
+  float* qpart = scratch_of_current_device(&rc);
+  if (!qpart) return rc;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  ScoreArgs s{};
+  s.pool.H = H; s.pool.L = 1; s.pool.bits = 16; s.pool.G = 64; s.pool.Tcap = round_up(P, kTile);
+  s.b.n_layers = 1; s.b.layer0 = 0;
+  s.b.q[0] = static_cast<const uint16_t*>(q.ptr);
+  s.b.q_sh = q.stride_head; s.b.q_st = q.stride_token;
+  s.ws.qpart_rows = H * kPoolSeg;
+  s.ws.sets = 1;
+  s.ws.qpart = qpart;  // every entry a call reads is written by that call's pooling kernel first: nothing to clear
+  s.ws.scores = scores;
+  s.ws.scores_stride = P;
+  s.Tc = P; s.n = n; s.n_special = n_s; s.pool_size = g; s.T_first = 0; s.P = P;
+  s.k_plain = static_cast<const uint16_t*>(k_mid_bf16);
+  if (launch_pool_query(s, stream) != hipSuccess || launch_score(s, stream) != hipSuccess) return XSV_ERR_HIP;
+  return XSV_OK;
 }
 
 int xsv_topk_keep(void* hip_stream, const float* scores, int P, int k, int T_first, int T_cur, int32_t* keep) {

@@ -43,7 +43,7 @@ class xsv_tensor(C.Structure):
 EXPORTS = (
     "xsv_create", "xsv_destroy", "xsv_reset", "xsv_dequant_attend", "xsv_frame_attend", "xsv_score_prune", "xsv_quantize",
     "xsv_step", "xsv_step_all_layers", "xsv_set_overlap", "xsv_join", "xsv_cache_len", "xsv_cache_export",
-    "xsv_cache_import", "xsv_last_selection", "xsv_quantize_k", "xsv_quantize_v", "xsv_score",
+    "xsv_cache_import", "xsv_last_selection", "xsv_quantize_k", "xsv_quantize_v", "xsv_score", "xsv_score_noalloc",
     "xsv_topk_keep", "xsv_strerror",
 )
 # every symbol include/xsv_tune.h declares (launch tuning and measurement aids)
@@ -91,6 +91,7 @@ def lib():
         L.xsv_quantize_k.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp, vp]
         L.xsv_quantize_v.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp, vp]
         L.xsv_score.argtypes = [vp, T, vp, i32, i32, i32, i32, i32, i32, vp]
+        L.xsv_score_noalloc.argtypes = [vp, T, vp, i32, i32, i32, i32, i32, i32, vp]
         L.xsv_topk_keep.argtypes = [vp, vp, i32, i32, i32, i32, vp]
         L.xsv_measure_peaks.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_float)]
         L.xsv_strerror.argtypes = [i32]
@@ -337,6 +338,19 @@ def score(q, k_mid, n_special, pool_size, stream=None):
     out = torch.empty(P, dtype=torch.float32, device=q.device)
     _check(lib().xsv_score(_stream_ptr(stream), as_tensor(q), k_mid.data_ptr(), H, n, n_special, P, d, pool_size,
                            out.data_ptr()), "xsv_score")
+    return out
+
+
+def score_noalloc(q, k_mid, n_special, pool_size, out, stream=None):
+    """xsv_score_noalloc: asynchronous on the stream, writes the caller's `out` (float32 device tensor [P])."""
+    H, n, d = q.shape
+    P = k_mid.shape[1]
+    if k_mid.dtype != torch.bfloat16 or not k_mid.is_contiguous():
+        raise ValueError("k_mid must be a contiguous bf16 device tensor [H][P][d]")
+    if out.dtype != torch.float32 or not out.is_contiguous() or out.numel() < P or not out.is_cuda:
+        raise ValueError("out must be a contiguous float32 device tensor of at least P elements")
+    _check(lib().xsv_score_noalloc(_stream_ptr(stream), as_tensor(q), k_mid.data_ptr(), H, n, n_special, P, d, pool_size,
+                                   out.data_ptr()), "xsv_score_noalloc")
     return out
 
 

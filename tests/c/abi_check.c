@@ -16,7 +16,7 @@ int main(void) {
                          (fn)xsv_quantize, (fn)xsv_step, (fn)xsv_step_all_layers,
                          (fn)xsv_cache_len, (fn)xsv_cache_export, (fn)xsv_cache_import,
                          (fn)xsv_last_selection, (fn)xsv_quantize_k, (fn)xsv_quantize_v,
-                         (fn)xsv_score, (fn)xsv_topk_keep, (fn)xsv_join,
+                         (fn)xsv_score, (fn)xsv_score_noalloc, (fn)xsv_topk_keep, (fn)xsv_join,
                          (fn)xsv_set_overlap, (fn)xsv_strerror,
                          /* xsv_tune.h */
                          (fn)xsv_set_attend_splits, (fn)xsv_set_attend_variant, (fn)xsv_set_side_cus,
