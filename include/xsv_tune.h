@@ -27,6 +27,10 @@ int xsv_set_side_cus(xsv_ctx* ctx, int compute_units);
  * range than the spare units allow, the extra one `percent` of a full range long (1..100, default 35; 0 = off): its
  * workgroups end early and hand their compute units to the chain for the rest of the attention launch. */
 int xsv_set_short_range(xsv_ctx* ctx, int percent);
+/* Tuning: what a key tile of the frame's own bf16 rows costs the attention kernel relative to a tile of the packed
+ * cache, in percent (25..400, default 95: bf16 rows need no dequantization).  When every (head, query block) is cut into the same key ranges, the
+ * ranges are chosen to cost the same by this measure, so that all workgroups of a launch end together. */
+int xsv_set_frame_tile_cost(xsv_ctx* ctx, int percent);
 /* Measurement aid.  While enabled, every attention launch of this context (xsv_dequant_attend, xsv_step,
  * xsv_step_all_layers) is bracketed by events on the context's stream: before the attention kernel,
  * between it and the kernel that merges key-range partials, after, and once more right behind.

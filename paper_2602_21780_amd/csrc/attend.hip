@@ -36,7 +36,12 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 constexpr int kLdsStride = 72;  // bf16 elements per LDS row: 64 + 8 pad (144 B, keeps 16 B alignment)
 constexpr int kLdsTile = 64 * kLdsStride;  // elements of one K (or V) tile in LDS
 constexpr float kNegBig = -1.0e30f;
-constexpr float kLazyLog2 = 8.0f;  // headroom of the lazily updated softmax reference, in powers of two
+// "no reference yet": with this in place of -reference every finite logit exponentiates to +infinity, which the
+// row-sum check catches, and the first real reference then scales the (empty) sums by 2^-huge = 0
+constexpr float kNoReference = 1.0e30f;
+// row sums may grow to this before the reference of the exponent is moved: 2^64 leaves the fp32 accumulators
+// (sums of probability x value over thousands of tokens) far from overflow
+constexpr float kSumLimit = 0x1p64f;
 
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
@@ -149,10 +154,19 @@ __device__ __forceinline__ void fetch_cache_tile(Stage<BITS, G, NH>& st, const R
         pz = rp.pz + t0 * (kD / G) + set;
         stride = kD / G;
       }
+      if (!rp.is_v || kD / G == 1) {  // consecutive parameters: 16-byte loads (t0 and o * kPer are multiples of 8)
 #pragma unroll
-      for (int e = 0; e < S::kPer; ++e) {
-        st.ps[set0][e] = ps[e * stride];
-        st.pz[set0][e] = pz[e * stride];
+        for (int e = 0; e < S::kPer; e += 4) {
+          const float4 a4 = *reinterpret_cast<const float4*>(ps + e), b4 = *reinterpret_cast<const float4*>(pz + e);
+          st.ps[set0][e] = a4.x; st.ps[set0][e + 1] = a4.y; st.ps[set0][e + 2] = a4.z; st.ps[set0][e + 3] = a4.w;
+          st.pz[set0][e] = b4.x; st.pz[set0][e + 1] = b4.y; st.pz[set0][e + 2] = b4.z; st.pz[set0][e + 3] = b4.w;
+        }
+      } else {
+#pragma unroll
+        for (int e = 0; e < S::kPer; ++e) {
+          st.ps[set0][e] = ps[e * stride];
+          st.pz[set0][e] = pz[e * stride];
+        }
       }
     }
   }
@@ -188,8 +202,8 @@ __device__ __forceinline__ void store_cache_tile(const Stage<BITS, G, NH>& st, u
 
 // Frame tiles (bf16 rows as given).  K half: 512 items of 16 bytes, item = (token i/8, channel run
 // i%8), copied as they are.  V half: the tile must land transposed ([channel][token]); an item is
-// (token octet i/32, channel pair i%32): eight 4-byte loads down the token axis (coalesced across
-// the 32 channel pairs of a row), two byte-permutes per register pair, and two 16-byte LDS writes.
+// (token octet, channel pair): eight 4-byte loads down the token axis (a wave's loads cover whole
+// 128-byte rows), two byte-permutes per register pair, and two 16-byte LDS writes.
 template <int NH>
 struct FrameStage {
   static constexpr int kIterK = 512 / NH;  // 16-byte items per K thread
@@ -198,29 +212,54 @@ struct FrameStage {
   uint32_t w[kIterK * 4];
 };
 
+// Frame tile, V half: which (channel pair c2 = 0..31, token octet tq) thread u of the V half stages first (its
+// further items are NH / 32 octets further down).  Eight consecutive lanes take four channel pairs of two
+// octets, so that their 16-byte LDS writes - rows 2 * c2 (+1) of 144 bytes, column 16 * tq - fall into eight
+// different bank groups; with consecutive channel pairs on consecutive lanes they would share four.
+__device__ __forceinline__ void frame_v_item(int u, int& c2, int& tq) {
+  const int l = u & 63, w = u >> 6;
+  c2 = 4 * (l >> 3) + (l & 3);
+  tq = 2 * w + ((l >> 2) & 1);
+}
+
+// The frame's rows are read through a buffer resource that covers exactly the n rows of the (layer, head): the
+// loads take one 32-bit offset register that never changes plus a scalar offset per tile (no 64-bit address per
+// load), and rows past the frame read as zeros by the resource's range check (their logits are masked, their
+// values must be finite).
+struct FrameRows {
+  __amdgpu_buffer_rsrc_t rsrc;
+  uint32_t row_bytes;  // stride between rows
+  uint32_t voff;       // this thread's byte offset inside a tile
+};
+
+__device__ __forceinline__ FrameRows frame_rows(const uint16_t* xh, int64_t x_st, int n, bool is_v, int u) {
+  FrameRows f;
+  f.row_bytes = (uint32_t)x_st * 2u;
+  const uint32_t bytes = ((uint32_t)(n - 1) * (uint32_t)x_st + (uint32_t)kD) * 2u;
+  f.rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(xh), 0, (int)bytes, 0x00020000);
+  // K: item (token u/8, channels 8*(u%8)..);  V: item (token octet u/32, channel pair u%32)
+  int c2, tq;
+  frame_v_item(u, c2, tq);
+  f.voff = is_v ? (uint32_t)(8 * tq) * f.row_bytes + 4u * c2 : (uint32_t)(u >> 3) * f.row_bytes + 16u * (u & 7);
+  return f;
+}
+
 template <int NH>
-__device__ __forceinline__ void fetch_frame_tile(FrameStage<NH>& st, const uint16_t* xh, int64_t x_st, bool is_v, int tile,
-                                                 int n, int u) {
+__device__ __forceinline__ void fetch_frame_tile(FrameStage<NH>& st, const FrameRows& f, bool is_v, int tile) {
   using F = FrameStage<NH>;
+  const uint32_t tile_off = (uint32_t)tile * kTile * f.row_bytes;  // scalar
   if (!is_v) {
 #pragma unroll
-    for (int it = 0; it < F::kIterK; ++it) {
-      const int i = u + it * NH;
-      const int row = tile * kTile + (i >> 3);
-      // rows past the frame: zeros (their logits are masked, their values must be finite)
-      const uint4 v = row < n ? *reinterpret_cast<const uint4*>(xh + (size_t)row * x_st + (i & 7) * 8) : make_uint4(0, 0, 0, 0);
-      st.w[4 * it] = v.x; st.w[4 * it + 1] = v.y; st.w[4 * it + 2] = v.z; st.w[4 * it + 3] = v.w;
+    for (int it = 0; it < F::kIterK; ++it) {  // items u + it * NH: NH / 8 rows further down
+      const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(f.rsrc, f.voff, tile_off + it * (NH / 8) * f.row_bytes, 0);
+      st.w[4 * it] = v[0]; st.w[4 * it + 1] = v[1]; st.w[4 * it + 2] = v[2]; st.w[4 * it + 3] = v[3];
     }
   } else {
 #pragma unroll
-    for (int it = 0; it < F::kIterV; ++it) {
-      const int i = u + it * NH;
-      const int c2 = i & 31, tq = i >> 5;
+    for (int it = 0; it < F::kIterV; ++it) {  // items u + it * NH: NH / 32 token octets further down
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int row = tile * kTile + 8 * tq + e;
-        st.w[8 * it + e] = row < n ? *reinterpret_cast<const uint32_t*>(xh + (size_t)row * x_st + 2 * c2) : 0u;
-      }
+      for (int e = 0; e < 8; ++e)
+        st.w[8 * it + e] = __builtin_amdgcn_raw_buffer_load_b32(f.rsrc, f.voff, tile_off + (it * (NH / 32) * 8 + e) * f.row_bytes, 0);
     }
   }
 }
@@ -238,8 +277,9 @@ __device__ __forceinline__ void store_frame_tile(const FrameStage<NH>& st, uint1
   } else {
 #pragma unroll
     for (int it = 0; it < F::kIterV; ++it) {
-      const int i = u + it * NH;
-      const int c2 = i & 31, tq = i >> 5;
+      int c2, tq;
+      frame_v_item(u, c2, tq);
+      tq += it * (NH / 32);
       uint32_t lo[4], hi[4];  // tokens 8tq.. of channel 2*c2 and of channel 2*c2+1
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
@@ -251,6 +291,13 @@ __device__ __forceinline__ void store_frame_tile(const FrameStage<NH>& st, uint1
     }
   }
 }
+
+// "No vector-memory load is outstanding here" as an instruction (s_waitcnt vmcnt(0)).  A tile loop fetches the next
+// tile under a condition and consumes it under the same condition further down; the compiler does not connect the
+// two, assumes that fetched registers may still be in flight on the path that skips the consumer, and would then
+// wait for ALL loads - the prefetch just issued included - in front of whatever reuses one of those registers in the
+// next iteration or the next loop.  Stated at the end of an iteration, where it is true anyway, it costs nothing.
+__device__ __forceinline__ void no_loads_in_flight() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
 // max of a value with the one held by the lane 32 apart (the other half of the same query's
 // tokens): one v_permlane32_swap instead of a round trip through the LDS crossbar
@@ -300,13 +347,15 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
 
   const int H = a.pool.H, n = a.n, Tc = a.Tc;
   const int nqb = (n + kRowsWG - 1) / kRowsWG;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  // the wave index as a scalar the compiler knows to be the same for all lanes: what depends on it - the staging
+  // role and every pointer chosen by it - lives in scalar registers, and the role's branches are scalar branches
+  const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int j = lane & 31, hh = lane >> 5;
   const int krow = tau(j);
   const float c2 = a.qscale;  // softmax scale * log2(e): p = 2^(c2 * (logit - max))
-  // staging role of this thread: first half of the workgroup K, second half V
-  const bool is_v = tid >= NH;
-  const int u = is_v ? tid - NH : tid;
+  // staging role of this wave: first half of the workgroup's waves K, second half V
+  const bool is_v = wave >= NW / 2;
+  const int u = (is_v ? wave - NW / 2 : wave) * 64 + lane;
 
   // tiles of a unit: cache blocks, then the frame's own tokens (each range padded to 64 on its own)
   const int n_ct = (Tc + kTile - 1) / kTile, n_ft = (n + kTile - 1) / kTile;
@@ -320,17 +369,25 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
     const int g = (slot / nqb) * 8 + xcd;  // (layer, head, key range) triple
     wg = ((g / a.xcd_ranges) * nqb + slot % nqb) * a.xcd_ranges + g % a.xcd_ranges;
   }
-  // start of workgroup w's piece on the (unit, tile) line; with `long_len` every unit is cut into
-  // equal_ranges - 1 ranges of long_len tiles and a last, shorter one (its workgroup ends early and
-  // leaves its compute unit to the kernels that run beside this one)
-  auto piece_begin = [&](int w) -> long long {
-    if (a.long_len <= 0) return part.begin(w);
-    const int un = w / a.equal_ranges, p = w % a.equal_ranges;
-    return (long long)un * part.n_tiles + min(p * a.long_len, part.n_tiles);
-  };
-  const long long piece_end = piece_begin(wg + 1);
+  // this workgroup's piece [piece_first, piece_end) of the (unit, tile) line: an equal share of the line, or - when
+  // every unit is cut into the same ranges - range wg % R of unit wg / R from the host's table of range starts
+  // (read with constant indices: a dynamically indexed kernel argument would be copied to scratch memory)
+  long long piece_first, piece_end;
+  if (a.equal_ranges <= 0) {
+    piece_first = part.begin(wg);
+    piece_end = part.begin(wg + 1);
+  } else {
+    const int un = wg / a.equal_ranges, p = wg % a.equal_ranges;
+    int b0 = 0, b1 = 0;
+#pragma unroll
+    for (int i = 0; i < kMaxPieces; ++i) {
+      if (i == p) { b0 = a.range_begin[i]; b1 = a.range_begin[i + 1]; }
+    }
+    piece_first = (long long)un * part.n_tiles + b0;
+    piece_end = (long long)un * part.n_tiles + b1;
+  }
 
-  for (long long pos = piece_begin(wg); pos < piece_end;) {
+  for (long long pos = piece_first; pos < piece_end;) {
   const int unit = part.unit_of(pos);
   const int t_begin = (int)(pos - (long long)unit * part.n_tiles);
   const int t_end = (int)min((long long)part.n_tiles, t_begin + (piece_end - pos));
@@ -370,20 +427,27 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
   const int n_cb = q_row0 >= n ? 0 : min(QB, (n - q_row0 + 31) / 32);
 
   f32x16 o0[QB], o1[QB];
-  float m[QB], l[QB];  // running max of the raw logits, this lane's share of the row sum
-  const float lazy_gap = kLazyLog2 / c2;
+  // softmax state per query block: mc = -(reference of the exponent, log2 domain) so that a probability is
+  // 2^(c2 * logit + mc), and this lane's share of the row sum
+  float mc[QB], l[QB];
 #pragma unroll
   for (int cb = 0; cb < QB; ++cb) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) { o0[cb][r] = 0.f; o1[cb][r] = 0.f; }
-    m[cb] = kNegBig;
+    mc[cb] = kNoReference;
     l[cb] = 0.f;
   }
-  // softmax of one query block over the 32 tokens of a half-step: masks tokens >= valid, moves the
-  // (lazy) reference maximum, exponentiates into packed bf16 and adds the row sums.  `hook(i)`,
-  // i = 0..3, is called before each quarter of the exponentials: the caller issues MFMAs there, so
-  // that the matrix pipe works underneath this arithmetic.
-  auto softmax_half = [&](f32x16& sv, u32x4 (&pb)[2], float& mref, float& lsum, f32x16& oa, f32x16& ob, int tok0,
+  // softmax of one query block over the 32 tokens of a half-step: masks tokens >= valid, exponentiates into
+  // packed bf16 and adds the row sums.  `hook(i)`, i = 0..3, is called before each quarter of the
+  // exponentials: the caller issues MFMAs there, so that the matrix pipe works underneath this arithmetic.
+  // The reference of the exponent is NOT the running row maximum: it stays where it is while the row sums
+  // stay below 2^kSumLog2 - probabilities above 1 are as exact as those below, in bf16 as in fp32 - and no
+  // maximum is computed at all on that path (half an instruction per logit saved).  Only when some row's sum
+  // passes the limit (or, the first time, when there is no reference yet: every finite logit then
+  // exponentiates to infinity) the block is redone the classical way: row maximum, new reference, sums and
+  // accumulators rescaled, probabilities recomputed.  The MFMAs of the hook belong to other blocks and are
+  // not repeated; this block's own PV product is issued by the caller after this function returns.
+  auto softmax_half = [&](f32x16& sv, u32x4 (&pb)[2], float& mcr, float& lsum, f32x16& oa, f32x16& ob, int tok0,
                           int valid, auto&& hook) {
     if (valid < tok0 + 32) {  // tokens past the end of the cache / of the frame
       // (the limit passes through an opaque move so that the 16 compares stay inside this rarely
@@ -395,30 +459,14 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
       for (int r = 0; r < 16; ++r)
         if (16 * (r >> 3) + (r & 7) >= lim) sv[r] = -INFINITY;
     }
-    float mx = fmaxf(fmaxf(sv[0], sv[1]), sv[2]);  // v_max3 chain
-#pragma unroll
-    for (int r = 3; r < 15; r += 2) mx = fmaxf(fmaxf(mx, sv[r]), sv[r + 1]);
-    mx = xhalf_max(fmaxf(mx, sv[15]));
-    // the reference maximum only moves when some row's maximum grows by more than 2^kLazyLog2;
-    // until then probabilities may exceed 1 (by at most that factor), which fp32 sums and
-    // bf16 products absorb, and the accumulators need no rescaling
-    if (__any(mx > mref + lazy_gap)) {  // lazy_gap = kLazyLog2 / c2: one add and one compare per half-step
-      const float m_new = fmaxf(mref, mx);
-      const float alpha = __builtin_amdgcn_exp2f((mref - m_new) * c2);
-      lsum *= alpha;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) { oa[r] *= alpha; ob[r] *= alpha; }
-      mref = m_new;
-    }
-    const float mc = -mref * c2;
     float psum = lsum;
 #pragma unroll
     for (int q4 = 0; q4 < 4; ++q4) {
       hook(q4);
 #pragma unroll
       for (int r = 4 * q4; r < 4 * q4 + 4; r += 2) {
-        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r], c2, mc));
-        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r + 1], c2, mc));
+        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r], c2, mcr));
+        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r + 1], c2, mcr));
         const uint32_t w = pack_bf16(p0, p1);
         pb[r >> 3][(r >> 1) & 3] = w;  // registers r = 8*k2 .. 8*k2+7 are the B operand of token step k2
         // row sum of the ROUNDED probabilities (what the PV product sees): v_dot2c_f32_bf16
@@ -426,11 +474,8 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
                                                psum, false);
       }
     }
-    // keep this block's probabilities in this block (the compiler would otherwise sink the
-    // exponentials down to their consumer, next to the MFMAs they are meant to overlap with)
-    asm volatile("" : "+v"(pb[0]), "+v"(pb[1]));
     // prescribed issue order of this block, per quarter: its MFMAs spread between its 12 vector
-    // instructions (4 fma, 4 exp, 2 convert, 2 dot) — the MFMAs execute while the VALU works
+    // instructions (4 fma, 4 exp, 2 convert, 2 dot) - the MFMAs execute while the VALU works
     constexpr int kMfmaPerQuarter = std::remove_reference_t<decltype(hook)>::kMfma;
     if constexpr (kMfmaPerQuarter > 0) {
 #pragma unroll
@@ -451,6 +496,34 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
         }
       }
     }
+    if (__builtin_expect(__any(!(psum <= kSumLimit)), 0)) {  // some row sum passed the limit (or is not finite): redo with a new reference
+      float mx = fmaxf(fmaxf(sv[0], sv[1]), sv[2]);  // v_max3 chain
+#pragma unroll
+      for (int r = 3; r < 15; r += 2) mx = fmaxf(fmaxf(mx, sv[r]), sv[r + 1]);
+      mx = xhalf_max(fmaxf(mx, sv[15]));  // both lane halves of a row agree on it
+      // new reference = max(old, row maximum of this half-step) in the log2 domain; rows whose tokens are all
+      // masked here keep theirs
+      const float ref_old = -mcr;
+      const float ref_new = fmaxf(ref_old, mx * c2);
+      const float alpha = __builtin_amdgcn_exp2f(ref_old - ref_new);  // 0 the first time (no reference yet)
+      lsum *= alpha;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { oa[r] *= alpha; ob[r] *= alpha; }
+      mcr = -ref_new;
+      psum = lsum;
+#pragma unroll
+      for (int r = 0; r < 16; r += 2) {
+        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r], c2, mcr));
+        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r + 1], c2, mcr));
+        const uint32_t w = pack_bf16(p0, p1);
+        pb[r >> 3][(r >> 1) & 3] = w;
+        psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), __builtin_bit_cast(bf16x2, 0x3f803f80u),
+                                               psum, false);
+      }
+    }
+    // keep this block's probabilities in this block (the compiler would otherwise sink the
+    // exponentials down to their consumer, next to the MFMAs they are meant to overlap with)
+    asm volatile("" : "+v"(pb[0]), "+v"(pb[1]));
     lsum = psum;
   };
 
@@ -496,19 +569,19 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
       for (int i = 0; i < 4; ++i) qk_step(sA, kf, 0, i);
       load_v(vf, 0);
       // ---- half 0 ----
-      softmax_half(sA, pA, m[0], l[0], o0[0], o1[0], 0, valid, with_mfma<1>([&](int i) { qk_step(sB, kf, 1, i); }));
+      softmax_half(sA, pA, mc[0], l[0], o0[0], o1[0], 0, valid, with_mfma<1>([&](int i) { qk_step(sB, kf, 1, i); }));
       load_k(kf, 1);
-      softmax_half(sB, pB, m[1], l[1], o0[1], o1[1], 0, valid, with_mfma<2>([&](int i) {
+      softmax_half(sB, pB, mc[1], l[1], o0[1], o1[1], 0, valid, with_mfma<2>([&](int i) {
         pv_step(0, vf, pA, i);
         qk_step(sA, kf, 0, i);
       }));
       // ---- half 1 ----
-      softmax_half(sA, pA, m[0], l[0], o0[0], o1[0], 32, valid, with_mfma<2>([&](int i) {
+      softmax_half(sA, pA, mc[0], l[0], o0[0], o1[0], 32, valid, with_mfma<2>([&](int i) {
         pv_step(1, vf, pB, i);
         qk_step(sB, kf, 1, i);
       }));
       load_v(vf, 1);
-      softmax_half(sB, pB, m[1], l[1], o0[1], o1[1], 32, valid, with_mfma<1>([&](int i) { pv_step(0, vf, pA, i); }));
+      softmax_half(sB, pB, mc[1], l[1], o0[1], o1[1], 32, valid, with_mfma<1>([&](int i) { pv_step(0, vf, pA, i); }));
 #pragma unroll
       for (int i = 0; i < 4; ++i) pv_step(1, vf, pB, i);
     } else {
@@ -523,7 +596,7 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
         load_v(vf, half);
         if (half == 0 && valid > 32) load_k(kf, 1);
         u32x4 pw[2];
-        softmax_half(sv, pw, m[0], l[0], o0[0], o1[0], 32 * half, valid, with_mfma<0>([](int) {}));
+        softmax_half(sv, pw, mc[0], l[0], o0[0], o1[0], 32 * half, valid, with_mfma<0>([](int) {}));
 #pragma unroll
         for (int i = 0; i < 4; ++i) pv_step(0, vf, pw, i);
       }
@@ -538,23 +611,28 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
     Stage<BITS, G, NH> st;
     fetch_cache_tile<BITS, G, NH>(st, rp, a.pool.Tcap, c_begin, u);
     store_cache_tile<BITS, G, NH>(st, rp.lds + cur * kLdsTile, u);
+    no_loads_in_flight();
     for (int t = c_begin; t < c_end; ++t) {
       __syncthreads();  // tile t is in lds[cur]; everybody is done reading lds[cur^1]
       if (t + 1 < c_end) fetch_cache_tile<BITS, G, NH>(st, rp, a.pool.Tcap, t + 1, u);
       compute(cur, min(kTile, Tc - t * kTile));
       if (t + 1 < c_end) store_cache_tile<BITS, G, NH>(st, rp.lds + (cur ^ 1) * kLdsTile, u);
+      no_loads_in_flight();
       cur ^= 1;
     }
   }
   if (f_begin < f_end) {
     FrameStage<NH> st;
-    fetch_frame_tile<NH>(st, xh, x_st, is_v, f_begin, n, u);
+    const FrameRows fr = frame_rows(xh, x_st, n, is_v, u);
+    fetch_frame_tile<NH>(st, fr, is_v, f_begin);
     store_frame_tile<NH>(st, rp.lds + cur * kLdsTile, is_v, u);  // lds[cur] was last read two barriers ago
+    no_loads_in_flight();
     for (int t = f_begin; t < f_end; ++t) {
       __syncthreads();
-      if (t + 1 < f_end) fetch_frame_tile<NH>(st, xh, x_st, is_v, t + 1, n, u);
+      if (t + 1 < f_end) fetch_frame_tile<NH>(st, fr, is_v, t + 1);
       compute(cur, min(kTile, n - t * kTile));
       if (t + 1 < f_end) store_frame_tile<NH>(st, rp.lds + (cur ^ 1) * kLdsTile, is_v, u);
+      no_loads_in_flight();
       cur ^= 1;
     }
   }
@@ -601,7 +679,7 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) op[i * 64] = make_uint4(hw[4 * i], hw[4 * i + 1], hw[4 * i + 2], hw[4 * i + 3]);
       if (hh == 0)
-        *reinterpret_cast<float4*>(a.ws.attn_ml + row * 4) = make_float4(m[cb] * c2, lsum, __builtin_amdgcn_ldexpf(1.0f, e), 0.f);
+        *reinterpret_cast<float4*>(a.ws.attn_ml + row * 4) = make_float4(-mc[cb], lsum, __builtin_amdgcn_ldexpf(1.0f, e), 0.f);
     }
   }
   }  // units of this workgroup's piece

@@ -67,6 +67,7 @@ struct xsv_ctx {
   size_t timing_used = 0;
   std::vector<hipEvent_t> chain_events;  // triples on the chain's stream: before score, after select, after re-quantize
   size_t chain_used = 0;
+  int frame_tile_cost = 95;  // cost of a key tile of the frame's own rows in percent of a cache tile's (attention range cut)
   int short_pct = 35; // xsv_step: length of one extra, short key range per unit, in percent of a long one (0 = none)
   int side_cus = -1;  // compute units xsv_step leaves to the prune chain while attention runs (-1: by launch size)
   size_t part_rows = 0;  // rows the partial-output workspace holds
@@ -79,7 +80,7 @@ namespace {
 int round_up(int a, int b) { return (a + b - 1) / b * b; }
 
 bool tensor_ok(const xsv_tensor& t) {
-  return t.ptr != nullptr && t.stride_token >= kD && t.stride_head >= 0 &&
+  return t.ptr != nullptr && t.stride_token >= kD && t.stride_token <= (1ll << 24) && t.stride_head >= 0 &&
          (reinterpret_cast<uintptr_t>(t.ptr) % 16 == 0) && t.stride_token % 8 == 0 && t.stride_head % 8 == 0;
 }
 
@@ -236,6 +237,29 @@ int fill_batch(xsv_ctx* ctx, Batch& b, int layer0, int n_layers, const xsv_tenso
   return XSV_OK;
 }
 
+// Where the R key ranges of a unit begin (begin[0] = 0 .. begin[R] = all tiles), so that every range costs the same:
+// a cache tile costs 100, a tile of the frame's own rows frame_cost; the last range gets last_pct percent of a
+// full share.  Every range holds at least one tile (R <= tiles).
+void range_starts(int n_ct, int n_ft, int R, int last_pct, int frame_cost, int16_t* begin) {
+  const int n_tiles = n_ct + n_ft;
+  const long long total = 100ll * n_ct + (long long)frame_cost * n_ft;
+  const long long shares = 100ll * (R - 1) + last_pct;  // in percent of a full share
+  begin[0] = 0;
+  long long acc = 0;
+  int t = 0;
+  for (int p = 1; p < R; ++p) {
+    const long long target = total * (100ll * p) / shares;  // cost in front of range p
+    while (t < n_tiles - (R - p)) {                         // leave one tile for each range still to come
+      const int c = t < n_ct ? 100 : frame_cost;
+      if (t > begin[p - 1] && acc + c / 2 >= target) break;  // not empty, and nearer to the target without this tile
+      acc += c;
+      ++t;
+    }
+    begin[p] = (int16_t)t;
+  }
+  begin[R] = (int16_t)n_tiles;
+}
+
 // The three stages for layers [layer0, layer0 + n_layers), which must be in step with each other.
 // frame_only: the frame's own tokens are the only keys (no cache tiles, no change of state).
 int do_attend(xsv_ctx* ctx, int layer0, int n_layers, const xsv_tensor* q, const xsv_tensor* k, const xsv_tensor* v,
@@ -249,19 +273,18 @@ int do_attend(xsv_ctx* ctx, int layer0, int n_layers, const xsv_tensor* q, const
   a.n = ctx->cfg.tokens_per_frame;
   a.variant = ctx->attend_variant;
   AttendPlan plan = choose_grid(ctx, n_layers, a.Tc, splits_req, spare_cus);
-  a.long_len = 0;
+  const int n_ct = (a.Tc + kTile - 1) / kTile, n_ft = (a.n + kTile - 1) / kTile, n_tiles = n_ct + n_ft;
+  bool short_last = false;
   if (splits_req <= 0 && spare_cus > 0 && ctx->short_pct > 0) {
     // beside the overlapped chain: the equal cut that leaves spare units, plus one short range per unit
     const int rows = attend_rows_per_workgroup(ctx->attend_variant);
     const int n_units = ((a.n + rows - 1) / rows) * ctx->cfg.n_heads * n_layers;
-    const int n_tiles = (a.Tc + kTile - 1) / kTile + (a.n + kTile - 1) / kTile;
     const int S = plan.n_wgs % n_units == 0 ? plan.n_wgs / n_units : 0;
-    if (S >= 1 && (S + 1) * n_units <= ctx->n_cu - 8 && S + 1 <= kMaxPieces) {
+    if (S >= 1 && (S + 1) * n_units <= ctx->n_cu - 8 && S + 1 <= kMaxPieces && S + 1 <= n_tiles) {
       const AttendPlan more = plan_attend(ctx->attend_variant, n_layers, ctx->cfg.n_heads, a.n, a.Tc, (S + 1) * n_units, ctx->part_rows);
-      const int len = (100 * n_tiles + 100 * S + ctx->short_pct - 1) / (100 * S + ctx->short_pct);
-      if (more.n_wgs == (S + 1) * n_units && len * S < n_tiles) {
+      if (more.n_wgs == (S + 1) * n_units) {
         plan = more;
-        a.long_len = len;
+        short_last = true;
       }
     }
   }
@@ -271,8 +294,9 @@ int do_attend(xsv_ctx* ctx, int layer0, int n_layers, const xsv_tensor* q, const
   {
     const int n_units = ((a.n + plan.rows_wg - 1) / plan.rows_wg) * ctx->cfg.n_heads * n_layers;
     const int ranges = plan.n_wgs % n_units == 0 ? plan.n_wgs / n_units : 0;
-    a.equal_ranges = ranges > 1 ? ranges : 0;
+    a.equal_ranges = (ranges > 1 && ranges <= kMaxPieces && ranges <= n_tiles) ? ranges : 0;
     a.xcd_ranges = (ranges > 0 && (ctx->cfg.n_heads * n_layers * ranges) % 8 == 0) ? ranges : 0;
+    if (a.equal_ranges > 0) range_starts(n_ct, n_ft, a.equal_ranges, short_last ? ctx->short_pct : 100, ctx->frame_tile_cost, a.range_begin);
   }
   ctx->last_attend_wgs = plan.n_wgs;
   a.qscale = ctx->cfg.softmax_scale * 1.4426950408889634f;
@@ -595,6 +619,12 @@ int xsv_last_attend_workgroups(xsv_ctx* ctx, int32_t* workgroups) {
 int xsv_set_short_range(xsv_ctx* ctx, int percent) {
   if (!ctx || percent < 0 || percent > 100) return XSV_ERR_ARG;
   ctx->short_pct = percent;
+  return XSV_OK;
+}
+
+int xsv_set_frame_tile_cost(xsv_ctx* ctx, int percent) {
+  if (!ctx || percent < 25 || percent > 400) return XSV_ERR_ARG;
+  ctx->frame_tile_cost = percent;
   return XSV_OK;
 }
 

@@ -107,6 +107,7 @@ struct Workspace {
 
 // ---- launchers (defined in the .hip files; every one only enqueues on `stream`) -----------------
 
+constexpr int kMaxPieces = 16;  // workgroups that may share one unit
 struct AttendArgs {
   CachePool pool;
   Batch b;
@@ -116,12 +117,14 @@ struct AttendArgs {
   int n_wgs;     // workgroups the (unit, tile) line is cut into (from plan_attend)
   int rows_wg;   // query rows per workgroup of this variant
   int cut;       // some unit is shared by several workgroups: partials are written and merged
-  int equal_ranges;  // > 0: every unit is cut into exactly this many key ranges
-  int long_len;      // > 0 (with equal_ranges): tiles of each range but the last, which takes the rest
+  int equal_ranges;  // > 0: every unit is cut into exactly this many key ranges, at the same tiles:
+  // range p of a unit is its tiles [range_begin[p], range_begin[p + 1]); chosen on the host so that the ranges
+  // COST the same (a tile of the frame's own bf16 rows takes longer to stage than a tile of packed codes), or
+  // so that the last one is deliberately short (see xsv_set_short_range)
+  int16_t range_begin[17];
   int xcd_ranges;  // > 0: every unit is cut into this many key ranges and the grid is permuted for L2 sharing
   float qscale;  // softmax scale * log2(e)
 };
-constexpr int kMaxPieces = 16;  // workgroups that may share one unit
 struct AttendPlan {
   int n_wgs, rows_wg, max_pieces;
 };

@@ -48,7 +48,7 @@ EXPORTS = (
 )
 # every symbol include/xsv_tune.h declares (launch tuning and measurement aids)
 TUNE_EXPORTS = (
-    "xsv_set_attend_splits", "xsv_set_attend_variant", "xsv_set_side_cus", "xsv_set_short_range",
+    "xsv_set_attend_splits", "xsv_set_attend_variant", "xsv_set_side_cus", "xsv_set_short_range", "xsv_set_frame_tile_cost",
     "xsv_last_attend_workgroups", "xsv_set_attend_timing", "xsv_attend_times", "xsv_chain_times", "xsv_measure_peaks",
 )
 
@@ -80,6 +80,7 @@ def lib():
         L.xsv_set_overlap.argtypes = [vp, i32]
         L.xsv_set_side_cus.argtypes = [vp, i32]
         L.xsv_set_short_range.argtypes = [vp, i32]
+        L.xsv_set_frame_tile_cost.argtypes = [vp, i32]
         L.xsv_last_attend_workgroups.argtypes = [vp, C.POINTER(C.c_int32)]
         L.xsv_set_attend_timing.argtypes = [vp, i32]
         L.xsv_chain_times.argtypes = [vp, C.POINTER(C.c_int32), C.POINTER(C.c_float), C.POINTER(C.c_float)]
@@ -213,6 +214,9 @@ class Context:
 
     def set_short_range(self, percent):
         _check(lib().xsv_set_short_range(self._h, int(percent)), "xsv_set_short_range")
+
+    def set_frame_tile_cost(self, percent):
+        _check(lib().xsv_set_frame_tile_cost(self._h, int(percent)), "xsv_set_frame_tile_cost")
 
     def set_side_cus(self, compute_units):
         _check(lib().xsv_set_side_cus(self._h, int(compute_units)), "xsv_set_side_cus")
