@@ -53,6 +53,11 @@ int xsv_last_attend_workgroups(xsv_ctx* ctx, int32_t* workgroups);
  * of 512 (e.g. 1041 tokens).  Other values: XSV_ERR_ARG.  Results agree to rounding. */
 int xsv_set_attend_variant(xsv_ctx* ctx, int variant);
 
+/* Measurement aid, synchronous.  The re-quantization leaves out blocks of 64 cached tokens that keep their place
+ * (the first frame's, or all old blocks of a cache that is not pruned) once re-quantizing them has reproduced them
+ * bit for bit: `settled` = (head, block) pairs of the layer in that state, `total` = (head, block) pairs it holds. */
+int xsv_settled_blocks(xsv_ctx* ctx, int layer, int32_t* settled, int32_t* total);
+
 /* Measurement aid, synchronous: two yardsticks of the current device - the rate of a loop of nothing but the bf16
  * MFMA instruction the attention kernel uses (TFLOP/s, all compute units busy) and of a plain streaming copy of
  * 512 MiB (GB/s, bytes read + bytes written).  Allocates and frees 1 GiB of temporaries; takes about 50 ms. */

@@ -11,7 +11,12 @@
 //   values: min/max over a token's channel group by wave shuffles; the codes are transposed
 //           through an LDS byte tile so the packed block is written [channel][token], the layout
 //           the attention kernel's PV product consumes.
-//   Writes go to the layer's OTHER buffer, so nothing is updated in place.
+//   Writes go to the layer's OTHER buffer, so nothing is updated in place - except in a cache that is never pruned
+//   (one buffer): there no row ever moves, a block is read and rewritten by its one workgroup, reads first.
+//   Blocks whose rows stay where they are (the first frame's, or every block of old rows while nothing is pruned) are
+//   re-quantized from their own dequantized values like everything else, but that reaches a fixed point after a
+//   round or two; the step that sees a block come out bit-identical flags it, and from then on it is skipped: both
+//   buffers hold it and re-quantizing it can only reproduce it.
 // HBM-bound: every retained element is read once (packed) and written once (packed).
 // Compiled with -ffp-contract=off; division is IEEE, rounding is nearest-even (rintf).
 #include "xsv_internal.h"
@@ -93,19 +98,27 @@ __global__ __launch_bounds__(256) void requant_kernel(const RequantArgs a) {
   const int layer = a.b.layer0 + lb;
   const int sb = a.b.src_buf(lb);
   const LayerCache src = layer_cache(a.pool, sb, layer);
-  const LayerCache dst = layer_cache(a.pool, sb ^ 1, layer);
+  const LayerCache dst = layer_cache(a.pool, a.pool.buffers == 1 ? sb : sb ^ 1, layer);
   const int32_t* keep = a.ws.keep + list_index(a.ws.sets, layer, h) * a.ws.scores_stride;
   const int nv = min(kTile, Tn - u * kTile);  // valid new positions in this block
 
+  // A block that holds the same cached rows as before the step and has already reproduced itself is final.
+  const bool candidate = u < a.stable_blocks;  // the same for the whole workgroup
+  uint8_t* const stable = a.stable_flag + ((size_t)layer * a.pool.H + h) * (Tcap / kTile) + u;
+  if (candidate && *stable) return;
+  unsigned changed = 0;  // candidate blocks: some code or parameter written differs from what was read
+
   if (tid == 0) k_unsafe = 0;  // (ordered before its readers and writers by the barriers of the key phase)
-  const int s_row = r < nv ? keep[u * kTile + r] : -1;
+  // source row: arithmetic where the keep list is known without reading it (no dependent load in front of the gather)
+  const int pos = u * kTile + r;
+  int s_row = -1;
+  if (r < nv) s_row = pos < a.identity_end ? pos : (pos >= Tn - a.n ? pos - (Tn - a.n) + Tc : keep[pos]);
   const bool row_valid = s_row >= 0;
   const bool from_cache = row_valid && s_row < Tc;
 
   // token ids travel with the rows (one copy per index set: head 0 writes the shared one)
   if ((h == 0 || a.ws.sets > 1) && cq == 0 && row_valid) {
     const size_t row0 = a.ws.sets > 1 ? (size_t)h * Tcap : 0;
-    const int pos = u * kTile + r;
     dst.tok_frame[row0 + pos] = from_cache ? src.tok_frame[row0 + s_row] : a.frame_id;
     dst.tok_index[row0 + pos] = from_cache ? src.tok_index[row0 + s_row] : s_row - Tc;
   }
@@ -143,6 +156,7 @@ __global__ __launch_bounds__(256) void requant_kernel(const RequantArgs a) {
   float x[16];
 #pragma unroll
   for (int e = 0; e < 16; ++e) x[e] = 0.f;
+  uint32_t k_in[kQuant ? kRowDw / 4 : 1] = {};  // the row's packed key codes as read (candidate blocks compare against them)
   if (from_cache) {
     if constexpr (kQuant) {
       const uint32_t* codes = reinterpret_cast<const uint32_t*>(src.kc) + ((size_t)h * Tcap + s_row) * kRowDw + cq * (kRowDw / 4);
@@ -150,7 +164,7 @@ __global__ __launch_bounds__(256) void requant_kernel(const RequantArgs a) {
       const float* kz = src.kz + ((size_t)h * (Tcap / G) + s_row / G) * kD + cq * 16;
       uint32_t w[kRowDw / 4];
 #pragma unroll
-      for (int i = 0; i < kRowDw / 4; ++i) w[i] = codes[i];
+      for (int i = 0; i < kRowDw / 4; ++i) w[i] = k_in[i] = codes[i];
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         const uint32_t code = (w[e / kPer] >> ((e % kPer) * BITS)) & kMask;
@@ -202,6 +216,7 @@ __global__ __launch_bounds__(256) void requant_kernel(const RequantArgs a) {
         gy[gi][c] = q.y;
         if (!q.safe) k_unsafe = 1;
         const size_t gidx = ((size_t)h * (Tcap / G) + (size_t)u * kKGroups + gi) * kD + c;
+        if (candidate) changed |= (__float_as_uint(src.ks[gidx]) ^ __float_as_uint(q.s)) | (__float_as_uint(src.kz[gidx]) ^ __float_as_uint(q.z));
         dst.ks[gidx] = q.s;
         dst.kz[gidx] = q.z;
       }
@@ -227,7 +242,10 @@ __global__ __launch_bounds__(256) void requant_kernel(const RequantArgs a) {
       }
       uint32_t* out = reinterpret_cast<uint32_t*>(dst.kc) + ((size_t)h * Tcap + (size_t)u * kTile + r) * kRowDw + cq * (kRowDw / 4);
 #pragma unroll
-      for (int i = 0; i < kRowDw / 4; ++i) out[i] = w[i];
+      for (int i = 0; i < kRowDw / 4; ++i) {
+        out[i] = w[i];
+        if (candidate) changed |= w[i] ^ k_in[i];
+      }
     }
   } else if (row_valid) {
     uint4* out = reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(dst.kc) + ((size_t)h * Tcap + (size_t)u * kTile + r) * kD + cq * 16);
@@ -274,12 +292,20 @@ __global__ __launch_bounds__(256) void requant_kernel(const RequantArgs a) {
       dst.vs[gidx] = q.s;
       dst.vz[gidx] = q.z;
     }
+    if (candidate && row_valid) changed |= (__float_as_uint(v_ps) ^ __float_as_uint(q.s)) | (__float_as_uint(v_pz) ^ __float_as_uint(q.z));
+    uint32_t vcode[16];
     if (__all(q.safe)) {
 #pragma unroll
-      for (int e = 0; e < 16; ++e) vt[cq * 16 + e][r] = row_valid ? (uint16_t)quant_code_fast(x[e], q.s, q.y, q.z, BITS) : (uint16_t)0;
+      for (int e = 0; e < 16; ++e) vcode[e] = quant_code_fast(x[e], q.s, q.y, q.z, BITS);
     } else {
 #pragma unroll
-      for (int e = 0; e < 16; ++e) vt[cq * 16 + e][r] = row_valid ? (uint16_t)quant_code(x[e], q.s, q.z, BITS) : (uint16_t)0;
+      for (int e = 0; e < 16; ++e) vcode[e] = quant_code(x[e], q.s, q.z, BITS);
+    }
+#pragma unroll
+    for (int e = 0; e < 16; ++e) vt[cq * 16 + e][r] = row_valid ? (uint16_t)vcode[e] : (uint16_t)0;
+    if (candidate && row_valid) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) changed |= vcode[e] ^ ((vraw[e] >> v_shift) & kMask);
     }
   } else {
 #pragma unroll
@@ -308,6 +334,10 @@ __global__ __launch_bounds__(256) void requant_kernel(const RequantArgs a) {
       out[0] = a0;
       out[1] = a1;
     }
+  }
+  if (candidate) {  // did the block reproduce itself?  (bf16 rows always do: they are copied)
+    const int any = __syncthreads_or(changed != 0);
+    if (tid == 0) *stable = any ? 0 : 1;
   }
 }
 

@@ -55,6 +55,7 @@ struct xsv_ctx {
   long long next_seq = 1;
   CachePool pool;
   Workspace ws;
+  uint8_t* stable_flag = nullptr;  // [L][H][Tcap / 64], see RequantArgs
   std::vector<LayerState> layers;
   std::vector<void*> allocs;
   int splits_single = 0, splits_batched = 0;
@@ -240,7 +241,7 @@ int fill_batch(xsv_ctx* ctx, Batch& b, int layer0, int n_layers, const xsv_tenso
 // Where the R key ranges of a unit begin (begin[0] = 0 .. begin[R] = all tiles), so that every range costs the same:
 // a cache tile costs 100, a tile of the frame's own rows frame_cost; the last range gets last_pct percent of a
 // full share.  Every range holds at least one tile (R <= tiles).
-void range_starts(int n_ct, int n_ft, int R, int last_pct, int frame_cost, int16_t* begin) {
+void range_starts(int n_ct, int n_ft, int R, int last_pct, int frame_cost, int32_t* begin) {
   const int n_tiles = n_ct + n_ft;
   const long long total = 100ll * n_ct + (long long)frame_cost * n_ft;
   const long long shares = 100ll * (R - 1) + last_pct;  // in percent of a full share
@@ -255,9 +256,9 @@ void range_starts(int n_ct, int n_ft, int R, int last_pct, int frame_cost, int16
       acc += c;
       ++t;
     }
-    begin[p] = (int16_t)t;
+    begin[p] = t;
   }
-  begin[R] = (int16_t)n_tiles;
+  begin[R] = n_tiles;
 }
 
 // The three stages for layers [layer0, layer0 + n_layers), which must be in step with each other.
@@ -373,12 +374,18 @@ int do_quantize(xsv_ctx* ctx, int layer0, int n_layers, const xsv_tensor* k, con
   r.n = ctx->cfg.tokens_per_frame;
   r.Tn = ctx->layers[layer0].pending_Tn;
   r.frame_id = ctx->layers[layer0].frames;
+  {
+    const PrunePlan p = plan_for(ctx->cfg, ctx->layers[layer0]);
+    r.identity_end = p.prune ? std::min(p.T_first, r.Tc) : r.Tc;
+    r.stable_blocks = r.identity_end / kTile;
+    r.stable_flag = ctx->stable_flag;
+  }
   if (launch_requant(r, ctx->work) != hipSuccess) return hip_fail(ctx);
   for (int i = 0; i < n_layers; ++i) {
     LayerState& L = ctx->layers[layer0 + i];
     L.T = r.Tn;
     L.frames += 1;
-    L.buf ^= 1;
+    if (ctx->pool.buffers == 2) L.buf ^= 1;
     L.phase = kIdle;
   }
   return XSV_OK;
@@ -487,7 +494,9 @@ int xsv_create(const xsv_config* cfg, void* hip_stream, xsv_ctx** out) {
   p.L = c.n_layers; p.H = c.n_heads; p.bits = c.kv_bits; p.G = c.group_size;
   p.Tcap = round_up((int)cap_tokens, kTile);
   p.sets = c.score_mode == 1 ? c.n_heads : 1;
-  const size_t slabs = 2 * (size_t)c.n_layers;
+  // a cache that is never pruned keeps every row where it is: one buffer, rewritten in place where a step touches it
+  p.buffers = c.budget == 0 ? 1 : 2;
+  const size_t slabs = (size_t)p.buffers * c.n_layers;
   int rc = XSV_OK;
   auto A = [&](auto** ptr, size_t count, bool zero) { if (rc == XSV_OK) rc = dev_alloc(ctx, ptr, count, zero); };
   // zero-filled: padding rows of a ragged last block are read (masked) by the attention kernel
@@ -507,6 +516,7 @@ int xsv_create(const xsv_config* cfg, void* hip_stream, xsv_ctx** out) {
   w.scores_stride = p.Tcap + (int)n;
   w.qpart_rows = c.n_heads * kPoolSeg;
   w.sets = p.sets;
+  A(&ctx->stable_flag, (size_t)c.n_layers * c.n_heads * (p.Tcap / kTile), true);
   A(&w.scores, (size_t)c.n_layers * w.sets * w.scores_stride, true);
   A(&w.keep, (size_t)c.n_layers * w.sets * w.scores_stride, true);
   A(&w.qpart, (size_t)c.n_layers * w.qpart_rows * kD, true);
@@ -541,6 +551,8 @@ int xsv_reset(xsv_ctx* ctx) {
   const int rc = join_layers(ctx, 0, ctx->cfg.n_layers);
   if (rc != XSV_OK) return rc;
   for (LayerState& L : ctx->layers) L = LayerState();
+  const size_t flags = (size_t)ctx->cfg.n_layers * ctx->cfg.n_heads * (ctx->pool.Tcap / kTile);
+  if (hipMemsetAsync(ctx->stable_flag, 0, flags, ctx->stream) != hipSuccess) return hip_fail(ctx);
   return XSV_OK;
 }
 
@@ -622,6 +634,23 @@ int xsv_set_short_range(xsv_ctx* ctx, int percent) {
   return XSV_OK;
 }
 
+int xsv_settled_blocks(xsv_ctx* ctx, int layer, int32_t* settled, int32_t* total) {
+  int rc = check_layer(ctx, layer);
+  if (rc != XSV_OK) return rc;
+  if (!settled || !total) return XSV_ERR_ARG;
+  if ((rc = settle_layer(ctx, layer)) != XSV_OK) return rc;
+  const size_t per_layer = (size_t)ctx->cfg.n_heads * (ctx->pool.Tcap / kTile);
+  std::vector<uint8_t> flags(per_layer);
+  if (hipMemcpyAsync(flags.data(), ctx->stable_flag + (size_t)layer * per_layer, per_layer, hipMemcpyDeviceToHost, ctx->stream) != hipSuccess ||
+      hipStreamSynchronize(ctx->stream) != hipSuccess)
+    return hip_fail(ctx);
+  int32_t count = 0;
+  for (uint8_t f : flags) count += f != 0;
+  *settled = count;
+  *total = ctx->cfg.n_heads * ((ctx->layers[layer].T + kTile - 1) / kTile);
+  return XSV_OK;
+}
+
 int xsv_set_frame_tile_cost(xsv_ctx* ctx, int percent) {
   if (!ctx || percent < 25 || percent > 400) return XSV_ERR_ARG;
   ctx->frame_tile_cost = percent;
@@ -678,7 +707,8 @@ int xsv_quantize(xsv_ctx* ctx, int layer, xsv_tensor k_new, xsv_tensor v_new) {
 // only waits for a layer's chain when it next needs that layer (or in xsv_join).
 static int step_layers(xsv_ctx* ctx, int layer0, int n_layers, const xsv_tensor* q, const xsv_tensor* k,
                        const xsv_tensor* v, void* const* out, int splits) {
-  const bool fork = ctx->overlap != 0;
+  // (a one-buffer cache is rewritten in place by the chain, so the chain must not run beside the attention that reads it)
+  const bool fork = ctx->overlap != 0 && ctx->pool.buffers == 2;
   {  // every tensor of the batch is checked before the first launch (the stages check again as they marshal)
     Batch probe;
     const int bad = fill_batch(ctx, probe, layer0, n_layers, q, k, v, out);
@@ -901,6 +931,10 @@ int xsv_cache_import(xsv_ctx* ctx, int layer, int32_t T, int32_t frames_seen, co
   for (int st = 0; T > 0 && st < p.sets; ++st)
     good = good && hipMemcpy(lc.tok_frame + (size_t)st * p.Tcap, token_frame + (size_t)st * T, (size_t)T * 4, hipMemcpyHostToDevice) == hipSuccess &&
            hipMemcpy(lc.tok_index + (size_t)st * p.Tcap, token_index + (size_t)st * T, (size_t)T * 4, hipMemcpyHostToDevice) == hipSuccess;
+  {  // nothing is known about the imported blocks
+    const size_t per_layer = (size_t)c.n_heads * (p.Tcap / kTile);
+    good = good && hipMemset(ctx->stable_flag + (size_t)layer * per_layer, 0, per_layer) == hipSuccess;
+  }
   if (!good) return hip_fail(ctx);
   L.T = T;
   L.frames = frames_seen;

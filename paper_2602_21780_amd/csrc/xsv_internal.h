@@ -37,6 +37,8 @@ struct CachePool {
   int32_t* tok_index;
   int L, H, Tcap, bits, G;
   int sets;  // retained index sets per layer: 1, or H when every head selects for itself
+  int buffers;  // 2: a step reads one buffer and writes the other; 1 (a cache that is never pruned: rows never move):
+                // a step rewrites the blocks it touches in place
 
   // slab = one (buffer, layer); sizes in elements of the respective array
   __host__ __device__ size_t code_row_bytes() const { return (size_t)kD * bits / 8; }
@@ -121,7 +123,7 @@ struct AttendArgs {
   // range p of a unit is its tiles [range_begin[p], range_begin[p + 1]); chosen on the host so that the ranges
   // COST the same (a tile of the frame's own bf16 rows takes longer to stage than a tile of packed codes), or
   // so that the last one is deliberately short (see xsv_set_short_range)
-  int16_t range_begin[17];
+  int32_t range_begin[17];
   int xcd_ranges;  // > 0: every unit is cut into this many key ranges and the grid is permuted for L2 sharing
   float qscale;  // softmax scale * log2(e)
 };
@@ -166,6 +168,14 @@ struct RequantArgs {
   Workspace ws;
   int Tc, n, Tn;  // old cache length, frame tokens, new cache length (= keep length)
   int frame_id;
+  // new positions [0, identity_end) keep their cache row (first frame, or everything cached when nothing is pruned),
+  // positions [Tn - n, Tn) are the frame's rows; only the positions in between are looked up in the keep list
+  int identity_end;
+  // the leading stable_blocks blocks of 64 positions hold the same cached rows as before the step (whole blocks inside
+  // [0, identity_end)): such a block is re-quantized from what it already holds, and once that reproduces it bit for
+  // bit - flagged per (layer, head, block) by the step that saw it happen - it never changes again and is skipped
+  int stable_blocks;
+  uint8_t* stable_flag;  // [L][H][Tcap / 64]
 };
 hipError_t launch_requant(const RequantArgs& a, hipStream_t stream);
 

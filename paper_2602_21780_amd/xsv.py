@@ -49,7 +49,7 @@ EXPORTS = (
 # every symbol include/xsv_tune.h declares (launch tuning and measurement aids)
 TUNE_EXPORTS = (
     "xsv_set_attend_splits", "xsv_set_attend_variant", "xsv_set_side_cus", "xsv_set_short_range", "xsv_set_frame_tile_cost",
-    "xsv_last_attend_workgroups", "xsv_set_attend_timing", "xsv_attend_times", "xsv_chain_times", "xsv_measure_peaks",
+    "xsv_last_attend_workgroups", "xsv_settled_blocks", "xsv_set_attend_timing", "xsv_attend_times", "xsv_chain_times", "xsv_measure_peaks",
 )
 
 _lib = None
@@ -83,6 +83,7 @@ def lib():
         L.xsv_set_frame_tile_cost.argtypes = [vp, i32]
         L.xsv_last_attend_workgroups.argtypes = [vp, C.POINTER(C.c_int32)]
         L.xsv_set_attend_timing.argtypes = [vp, i32]
+        L.xsv_settled_blocks.argtypes = [vp, i32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
         L.xsv_chain_times.argtypes = [vp, C.POINTER(C.c_int32), C.POINTER(C.c_float), C.POINTER(C.c_float)]
         L.xsv_attend_times.argtypes = [vp, C.POINTER(C.c_int32), C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_float)]
         L.xsv_cache_len.argtypes = [vp, i32, C.POINTER(C.c_int32)]
@@ -208,6 +209,12 @@ class Context:
         w = C.c_int32()
         _check(lib().xsv_last_attend_workgroups(self._h, C.byref(w)), "xsv_last_attend_workgroups")
         return w.value
+
+    def settled_blocks(self, layer=0):
+        """((head, block) pairs the re-quantization no longer touches, (head, block) pairs in the layer's cache)."""
+        a, b = C.c_int32(), C.c_int32()
+        _check(lib().xsv_settled_blocks(self._h, layer, C.byref(a), C.byref(b)), "xsv_settled_blocks")
+        return a.value, b.value
 
     def join(self):
         _check(lib().xsv_join(self._h), "xsv_join")

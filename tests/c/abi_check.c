@@ -20,7 +20,7 @@ int main(void) {
                          (fn)xsv_set_overlap, (fn)xsv_strerror,
                          /* xsv_tune.h */
                          (fn)xsv_set_attend_splits, (fn)xsv_set_attend_variant, (fn)xsv_set_side_cus,
-                         (fn)xsv_set_short_range, (fn)xsv_set_frame_tile_cost, (fn)xsv_last_attend_workgroups, (fn)xsv_set_attend_timing,
+                         (fn)xsv_set_short_range, (fn)xsv_set_frame_tile_cost, (fn)xsv_last_attend_workgroups, (fn)xsv_settled_blocks, (fn)xsv_set_attend_timing,
                          (fn)xsv_attend_times, (fn)xsv_chain_times, (fn)xsv_measure_peaks};
   size_t i;
   memset(&cfg, 0, sizeof cfg);

@@ -152,6 +152,28 @@ def test_unbounded_bf16_cache_matches_brute_force_attention():
     run_stream(spec, 5)
 
 
+@pytest.mark.parametrize("bits,G", [(16, 64), (4, 64), (2, 32)])
+def test_unpruned_cache_is_rewritten_in_place_and_settles(bits, G):
+    """A cache without a budget keeps one buffer: every step rewrites only the block the frame is appended to and the
+    old blocks that re-quantization has not yet reproduced bit for bit; the rest is left alone.  Every byte
+    against the oracle (which re-quantizes everything every step), and the count of settled blocks grows."""
+    spec = CONFIGS[0].with_(name=f"inplace-b{bits}", n_heads=3, tokens_per_frame=150, budget=0, kv_bits=bits, group_size=G,
+                            n_layers=2, seed=41)
+    ctx, st = parity.make_pair(spec, max_frames=12)
+    src = FrameSource(spec, DEV)
+    settled = []
+    for f in range(12):
+        q, k, v = src.frame(f)
+        for l in range(spec.n_layers):
+            parity.step_and_compare(ctx, st, spec, l, l, q[l], k[l], v[l], budget=0)
+        settled.append(ctx.settled_blocks(1)[0])
+    print("  settled (head, block) pairs per frame:", settled, flush=True)
+    full_old_blocks = 3 * ((11 * 150) // 64)           # heads x whole blocks of tokens cached before the last step
+    assert settled[-1] >= full_old_blocks - 3 * 6      # all but the most recent blocks (a couple of rounds to settle)
+    assert all(b >= a for a, b in zip(settled, settled[1:]))
+    ctx.destroy()
+
+
 @pytest.mark.parametrize("rising", [True, False])
 @pytest.mark.parametrize("bits,splits", [(16, 1), (4, 1), (4, 3)])
 def test_logits_that_drift_far_along_the_key_axis(rising, bits, splits):
