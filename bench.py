@@ -23,15 +23,11 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X dense bf16
 PEAK_HBM_GBS = 8000.0
-# HBM bytes of one attend_kernel launch of this workload (fetch 30.3 MB + write 25.7 MB), from the two
-# rocprofv3 --pmc runs summarized in profiles/attend_cfg2_hbm_traffic.md; not measurable from inside this
-# process, so it is carried here and only reported for the grid it was measured on.
-# Vector instructions (wave level, rocprofv3 SQ_INSTS_VALU) of one requant_kernel launch over all 24 layers of this
-# workload, from profiles/requant_cfg2_valu_counters.md, and the chip's vector issue peak: 256 compute units x 4 SIMDs,
-# one instruction per 4 cycles at 2.4 GHz.
-REQUANT_VALU_CFG2_24_LAYERS = 86.57e6
-PEAK_VALU_GINSTR = 256 * 4 * 2.4 / 4.0
-TRAFFIC_ATTEND_CFG2 = {"workgroups": 240, "bytes": 56.0e6}
+# Not measurable from inside this process: HBM bytes per attend_kernel launch of this workload from the two
+# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) summarized in profiles/attend_cfg2_hbm_traffic.md.  Reported under
+# "traffic_from_profile" with the profile's date and only for the grid it was measured on; "traffic" itself stays null.
+TRAFFIC_PROFILE = {"file": "profiles/attend_cfg2_hbm_traffic.md", "date": "2026-11-28", "workgroups": 240,
+                   "fetch_bytes": 24.7e6, "write_bytes": 15.8e6}
 
 
 def algorithmic_work(spec, Tc, Tn, P):
@@ -95,15 +91,16 @@ def main():
     if args.side_cus >= -1:
         ctx.set_side_cus(args.side_cus)
     packed = [ctx.pack_layers(q, k, v, out) for (q, k, v) in frames]
+    # one layer's arguments marshalled once per frame buffer (pointers and strides do not change between frames)
+    packed_steps = [[ctx.pack_step(q[l], k[l], v[l], out[l]) for l in range(L)] for (q, k, v) in frames]
     torch.cuda.synchronize()
 
     def run_frame(f, mode):
         if mode == "batched":
             ctx.step_all_layers(packed=packed[f])
         else:
-            q, k, v = frames[f]
             for l in range(L):
-                ctx.step(l, q[l], k[l], v[l], out[l])
+                ctx.step_packed(l, packed_steps[f][l])
         ctx.join()   # the frame's last re-quantization is ordered before whatever follows on the stream
 
     def timed(mode, f0, count):
@@ -114,36 +111,57 @@ def main():
         torch.cuda.synchronize()
         return time.perf_counter() - t0
 
-    for f in range(W):
-        run_frame(f, args.mode)
+    def warm(mode):
+        ctx.join()
+        ctx.reset()
+        for f in range(W):
+            run_frame(f, mode)
+
+    warm(args.mode)
     Tc = ctx.cache_len(0)
-    elapsed = timed(args.mode, W, K)
+    elapsed = timed(args.mode, W, K)          # THE timed region: exactly K frames
     ms_per_step = elapsed / K * 1e3
     value = K / elapsed
-
     step_wgs = ctx.last_attend_workgroups()   # attention grid of the timed steps
+    Tn = ctx.cache_len(0)
+    P = Tc + n - 2 * n
+    work = algorithmic_work(spec, Tc, Tn, P)
 
-    # the other launch form on the same frames, for context (off by default: it launches the same
-    # kernels in other shapes, which would blur a per-kernel profile of this command)
+    # ---- the dominant kernel inside the timed configuration -------------------------------------------------
+    # The same K frames again, free-running as above (chain beside attention, joins deferred), now with the
+    # library's events around every attention launch on the launch stream: before the attention kernel, between it
+    # and the merge kernel, after, and one more right behind (the last pair has nothing between its events: its span
+    # is what an event pair itself adds, and is taken off).  These are the launches ms_per_step is made of.
+    warm(args.mode)
+    ctx.set_attend_timing(True)
+    elapsed_with_events = timed(args.mode, W, K)
+    n_timed_launches, attend_span_ms, merge_span_ms, event_ms = ctx.attend_times()
+    ctx.set_attend_timing(False)
+    attend_kernel_ms, merge_kernel_ms = attend_span_ms - event_ms, merge_span_ms - event_ms
+    attend_tflops = work["attend_flop"] / (attend_kernel_ms * 1e-3) / 1e12
+
+    # the library's default sequencing (every step joins its chain before it returns), same frames
+    default_fps = None
+    if args.overlap != 1:
+        ctx.set_overlap(1)
+        warm(args.mode)
+        default_fps = K / timed(args.mode, W, K)
+        ctx.set_overlap(args.overlap)
+
+    # the other launch form on the same frames, for context
     other, other_fps = ("batched" if args.mode == "layerwise" else "layerwise"), None
     if args.both_forms:
-        ctx.reset()
-        for f in range(W):
-            run_frame(f, other)
+        warm(other)
         other_fps = K / timed(other, W, K)
-        ctx.reset()
-        for f in range(W):
-            run_frame(f, args.mode)
 
-    # ---- per-stage durations with events on the launch stream (steady state) --------------------------
-    # Each stage is launched for all 24 layers back to back between two events (the layers are
-    # independent of each other), so one event pair brackets 24 launches and its own cost is amortized.
-    # The attention launches are additionally bracketed inside the library (before the attention
-    # kernel, between it and the merge kernel, after), which separates the two kernels.
+    # ---- per-stage durations, each stage alone (nothing beside it), events on the launch stream ------------------
+    # Each stage is launched for all 24 layers back to back between two events (the layers are independent of each
+    # other), so one event pair brackets 24 launches and its own cost is amortized.
+    warm(args.mode)
     ctx.join()
     n_units = spec.n_heads * ((n + 511) // 512)
     if args.splits == 0 and step_wgs % n_units == 0:
-        ctx.set_attend_splits(step_wgs // n_units, 0)   # the grid the timed steps used (they leave units to the chain)
+        ctx.set_attend_splits(step_wgs // n_units, 0)   # as many key ranges as the timed steps used
     ev = lambda: torch.cuda.Event(enable_timing=True)
     stage_ms = {"attend": 0.0, "score_prune": 0.0, "quantize": 0.0}
 
@@ -166,33 +184,38 @@ def main():
         torch.cuda.synchronize()
         return marks
 
-    marks = stage_pass(W + K)                      # amortized: one event pair per 24 launches of a stage
+    marks = stage_pass(W)
     for e in marks:
         stage_ms["attend"] += e[0].elapsed_time(e[1]) / (L * len(marks))
         stage_ms["score_prune"] += e[1].elapsed_time(e[2]) / (L * len(marks))
         stage_ms["quantize"] += e[2].elapsed_time(e[3]) / (L * len(marks))
     ctx.set_attend_timing(True)                    # the same again with the library's events around each kernel
-    stage_pass(W + K + S)
-    n_timed_launches, attend_span_ms, merge_span_ms, event_ms = ctx.attend_times()
+    stage_pass(W + S)
+    iso_launches, iso_attend_span, iso_merge_span, iso_event = ctx.attend_times()
     ctx.set_attend_timing(False)
-    # a span between two events holds the kernel plus what the closing event itself takes
-    attend_kernel_ms, merge_kernel_ms = attend_span_ms - event_ms, merge_span_ms - event_ms
-    Tn = ctx.cache_len(0)
-    P = Tc + n - 2 * n
-    work = algorithmic_work(spec, Tc, Tn, P)
-    attend_tflops = work["attend_flop"] / (attend_kernel_ms * 1e-3) / 1e12
+    iso_attend_ms = iso_attend_span - iso_event
+    traffic_from_profile = None
+    if TRAFFIC_PROFILE["fetch_bytes"] is not None and step_wgs == TRAFFIC_PROFILE["workgroups"]:
+        traffic_from_profile = dict(TRAFFIC_PROFILE, bytes=TRAFFIC_PROFILE["fetch_bytes"] + TRAFFIC_PROFILE["write_bytes"],
+                                    ratio_to_algorithmic=round((TRAFFIC_PROFILE["fetch_bytes"] + TRAFFIC_PROFILE["write_bytes"]) / work["attend_bytes"], 2))
     roofline = {
         "kernel": "attend_kernel<4,64,8,2>",
         "bound": "mfma", "achieved": round(attend_tflops, 2), "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
         "frac": round(attend_tflops / PEAK_BF16_MFMA_TFLOPS, 4),
-        "traffic": TRAFFIC_ATTEND_CFG2["bytes"] if ctx.last_attend_workgroups() == TRAFFIC_ATTEND_CFG2["workgroups"] else None,
-        "traffic_unit": "bytes per attend_kernel launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, profiles/attend_cfg2_hbm_traffic.md)",
+        "traffic": None, "traffic_from_profile": traffic_from_profile,
+        "measured_on": "the launches of a second pass over the timed frames in the timed configuration (chain beside "
+                       "attention, deferred joins), events of the library on the launch stream around every launch",
         "algorithmic_bytes": work["attend_bytes"],
         "flop_per_launch": work["attend_flop"], "avg_launch_ms": round(attend_kernel_ms, 4), "launches_timed": n_timed_launches,
-        "workgroups": ctx.last_attend_workgroups(),
+        "workgroups": step_wgs,
         "merge_kernel_ms": round(merge_kernel_ms, 4), "event_pair_ms": round(event_ms, 4),
-        "attend_plus_merge_ms": round(stage_ms["attend"], 4),
-        "attend_plus_merge_TFLOPs": round(work["attend_flop"] / (stage_ms["attend"] * 1e-3) / 1e12, 2),
+        "attend_plus_merge_TFLOPs": round(work["attend_flop"] / ((attend_kernel_ms + merge_kernel_ms) * 1e-3) / 1e12, 2),
+        "frames_per_s_with_events": round(K / elapsed_with_events, 2),
+        "isolated": {   # attention launches alone, 24 back to back, nothing running beside them
+            "avg_launch_ms": round(iso_attend_ms, 4), "merge_kernel_ms": round(iso_merge_span - iso_event, 4),
+            "launches_timed": iso_launches, "TFLOPs": round(work["attend_flop"] / (iso_attend_ms * 1e-3) / 1e12, 2),
+            "attend_plus_merge_ms": round(stage_ms["attend"], 4),
+        },
     }
     hbm = {
         "score_prune_GBs": round(work["score_bytes"] / (stage_ms["score_prune"] * 1e-3) / 1e9, 1),
@@ -222,11 +245,6 @@ def main():
     }
     hbm["all_layers_per_launch"]["score_prune_frac"] = round(hbm["all_layers_per_launch"]["score_prune_GBs"] / PEAK_HBM_GBS, 4)
     hbm["all_layers_per_launch"]["quantize_frac"] = round(hbm["all_layers_per_launch"]["quantize_GBs"] / PEAK_HBM_GBS, 4)
-    if spec.name == "cfg2-24-layer" and rq_ms > 0:
-        ginstr = REQUANT_VALU_CFG2_24_LAYERS / (rq_ms * 1e-3) / 1e9
-        hbm["all_layers_per_launch"]["quantize_alu"] = {
-            "bound": "alu", "achieved": round(ginstr, 1), "peak": round(PEAK_VALU_GINSTR, 1),
-            "unit": "G vector instructions/s (wave level)", "frac": round(ginstr / PEAK_VALU_GINSTR, 4)}
 
     # ---- the oracle on the host cores, bounded sample ------------------------------------------------
     cpu = None
@@ -267,6 +285,7 @@ def main():
                    "attend_key_splits": args.splits or "auto", "overlap_mode": args.overlap},
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "frames_per_s_default_mode": round(default_fps, 2) if default_fps else None,
         "other_launch_form": {"form": other, "frames_per_s": round(other_fps, 2)} if other_fps else None,
         "attention_TFLOPs_whole_step": round(work["attend_flop"] * L * value / 1e12, 2),
         "hbm_stages": hbm,

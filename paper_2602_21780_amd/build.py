@@ -8,6 +8,7 @@ from concurrent.futures import ThreadPoolExecutor
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libxsv.so")
+ISSUE_BENCH = os.path.join(_HERE, "issue_bench")   # standalone microbenchmark program (csrc/issue_bench.hip)
 BUILD_DIR = os.path.join(_HERE, "_build")
 
 # packed-fp32 instructions are switched off for every kernel (target feature): some of their forms have
@@ -53,6 +54,10 @@ def build(verbose: bool = False) -> str:
     r = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stderr}")
+    r = subprocess.run([hipcc, *[f for f in COMMON if f != "-fPIC"], "-Wno-unused-result", "-mllvm", "-amdgpu-mfma-vgpr-form=1",
+                        os.path.join(CSRC, "issue_bench.hip"), "-o", ISSUE_BENCH], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"issue_bench failed to build:\n{r.stderr}")
     return LIB
 
 

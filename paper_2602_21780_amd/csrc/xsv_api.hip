@@ -69,7 +69,7 @@ struct xsv_ctx {
   std::vector<hipEvent_t> chain_events;  // triples on the chain's stream: before score, after select, after re-quantize
   size_t chain_used = 0;
   int frame_tile_cost = 95;  // cost of a key tile of the frame's own rows in percent of a cache tile's (attention range cut)
-  int short_pct = 35; // xsv_step: length of one extra, short key range per unit, in percent of a long one (0 = none)
+  int short_pct = 50; // xsv_step: length of one extra, short key range per unit, in percent of a long one (0 = none)
   int side_cus = -1;  // compute units xsv_step leaves to the prune chain while attention runs (-1: by launch size)
   size_t part_rows = 0;  // rows the partial-output workspace holds
   int n_cu = 256;

@@ -256,6 +256,13 @@ class Context:
         _check(lib().xsv_step(self._h, layer, as_tensor(q), as_tensor(k_new), as_tensor(v_new), out.data_ptr()), "xsv_step")
         return out
 
+    def pack_step(self, q, k_new, v_new, out):
+        """Marshal one layer's tensors once, for repeated step_packed calls (the tensors must stay alive)."""
+        return as_tensor(q), as_tensor(k_new), as_tensor(v_new), out.data_ptr()
+
+    def step_packed(self, layer, packed):
+        _check(lib().xsv_step(self._h, layer, *packed), "xsv_step")
+
     def pack_layers(self, q, k_new, v_new, out):
         """Marshal per-layer tensors ([L][H][n][d] or lists) once, for repeated step_all_layers calls."""
         L = self.cfg.n_layers
