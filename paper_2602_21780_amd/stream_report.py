@@ -8,6 +8,7 @@ per-frame cost stay constant; Sec. 4.4 reports the same comparison on video stre
     python -m paper_2602_21780_amd.stream_report --granularity
     python -m paper_2602_21780_amd.stream_report --selector-sweep
     python -m paper_2602_21780_amd.stream_report --frame-attention
+    python -m paper_2602_21780_amd.stream_report --requant-study 300
 
 `--configs`: frames/s of each listed workload at its saturated cache, layer by layer through xsv_step
 (overlap mode 2, one xsv_join per frame), events on the launch stream around each frame's 24 (or 1) steps.
@@ -23,6 +24,9 @@ selector (score_mode 1), pruning without quantization and quantization without p
 paper's cache-length ablation (Sec. 4.5) with output error standing in for the task metrics.
 `--frame-attention`: the frame-wise attention of the alternating backbone (xsv_frame_attend: a frame's tokens over
 themselves) at 1374 and 1041 tokens, 16 heads: time per launch over 24 x 20 launches issued back to back.
+`--requant-study N`: one layer of the long stream for N frames: how many retained rows a re-quantization step leaves
+bit-identical, the error of cached rows against the rows the frames delivered by time spent in the cache, and the
+number of parameter rows a cache that quantized every token only once would have to keep (Sec. 3.3).
 Inputs are synthetic (seeded), generated on the device outside the timed regions.  One JSON line per row.
 """
 from __future__ import annotations
@@ -128,6 +132,78 @@ def selector_sweep(torch, xsv, FrameSource, CONFIGS, frames=14):
     return rows
 
 
+def requant_study(torch, xsv, FrameSource, CONFIGS, frames):
+    """What re-quantizing the whole retained cache every step (Sec. 3.3: quantization is applied to the final cache
+    of a step) does to tokens that stay for many steps, on one layer of the long drifting stream:
+      - how many retained value rows / key groups come out of a step bit-identical to what went in (a row that does
+        is a fixed point: carrying its codes over would give the same bytes);
+      - the error of the cached (dequantized) rows against the ORIGINAL bf16 rows the frames delivered, by how long
+        a token has been cached - against the error of a single quantization (tokens of the newest frame);
+      - what a cache that quantized every token ONCE (immutable key groups of 64 consecutive tokens of a frame) would
+        have to keep: the number of distinct (frame, group) parameter rows its retained middle tokens point to.
+    Runs on the device through xsv_step / xsv_cache_export; the bookkeeping is host-side numpy."""
+    import numpy as np
+    from paper_2602_21780_amd.inputs import to_u16
+    spec = CONFIGS[3].with_(n_layers=1, frames=frames)
+    n, H, G = spec.tokens_per_frame, spec.n_heads, spec.group_size
+    ctx = xsv.Context.from_spec(spec)
+    src = FrameSource(spec, "cuda:0", layers=[0])
+    f32 = lambda u16: (np.asarray(u16, np.uint32) << 16).view(np.float32)
+    orig_k = orig_v = None           # [H][T][d] fp32: what the frames delivered for the tokens now cached
+    prev = None                      # last step's export, and token ids -> row
+    rows = []
+    buckets = ((0, 0), (1, 1), (2, 5), (6, 20), (21, 100), (101, 10 ** 9))
+    acc = {b: {"k_se": 0.0, "v_se": 0.0, "k_ref": 0.0, "v_ref": 0.0, "count": 0} for b in buckets}
+    same_v = same_k = seen_v = seen_k = 0
+    once_groups = []
+    for f in range(frames):
+        q, k, v = src.frame(f)
+        ctx.step(0, q[0], k[0], v[0])
+        _, keep = ctx.last_selection(0)
+        kf, vf = f32(to_u16(k[0])), f32(to_u16(v[0]))
+        both_k = kf if orig_k is None else np.concatenate([orig_k, kf], axis=1)
+        both_v = vf if orig_v is None else np.concatenate([orig_v, vf], axis=1)
+        orig_k, orig_v = both_k[:, keep], both_v[:, keep]
+        c = ctx.cache_export(0)
+        age = f - c.token_frame                                     # frames a token has been cached
+        if prev is not None:
+            # rows kept from the previous cache: position in the old cache = keep[i] for keep[i] < T_old
+            old = keep[keep < prev.T]
+            new_pos = np.nonzero(keep < prev.T)[0]
+            v_same = (np.all(c.v_codes[:, new_pos] == prev.v_codes[:, old], axis=2)
+                      & np.all(c.v_scale[:, new_pos] == prev.v_scale[:, old], axis=2)
+                      & np.all(c.v_zero[:, new_pos] == prev.v_zero[:, old], axis=2))
+            same_v += int(v_same.sum()); seen_v += v_same.size
+            k_same = np.all(c.k_codes[:, new_pos] == prev.k_codes[:, old], axis=2)     # key rows: codes only
+            same_k += int(k_same.sum()); seen_k += k_same.size
+        if f >= 5:
+            kd, vd = f32(c.k_bf16), f32(c.v_bf16)
+            for b in buckets:
+                sel = (age >= b[0]) & (age <= b[1])
+                if sel.any():
+                    a = acc[b]
+                    a["k_se"] += float(((kd[:, sel] - orig_k[:, sel]) ** 2).sum()); a["k_ref"] += float((orig_k[:, sel] ** 2).sum())
+                    a["v_se"] += float(((vd[:, sel] - orig_v[:, sel]) ** 2).sum()); a["v_ref"] += float((orig_v[:, sel] ** 2).sum())
+                    a["count"] += int(sel.sum())
+            mid = (np.arange(c.T) >= n) & (np.arange(c.T) < c.T - n)
+            once_groups.append(len(set(zip(c.token_frame[mid].tolist(), (c.token_index[mid] // G).tolist()))))
+        prev = c
+    ctx.destroy()
+    rows.append({"study": "bit-identical after a re-quantization step", "frames": frames,
+                 "value_rows_identical": round(same_v / max(seen_v, 1), 5), "value_rows_seen": seen_v,
+                 "key_rows_with_identical_codes": round(same_k / max(seen_k, 1), 5), "key_rows_seen": seen_k})
+    for b in buckets:
+        a = acc[b]
+        if a["count"]:
+            rows.append({"study": "error against the original bf16 rows", "cached_for_frames": f"{b[0]}..{b[1] if b[1] < 10 ** 9 else 'end'}",
+                         "tokens_averaged": a["count"], "key_rel_rms": round((a["k_se"] / a["k_ref"]) ** 0.5, 5),
+                         "value_rel_rms": round((a["v_se"] / a["v_ref"]) ** 0.5, 5)})
+    rows.append({"study": "parameter rows a quantize-once cache would hold for the retained middle (groups of 64 tokens of a frame)",
+                 "mean": round(float(np.mean(once_groups)), 1), "max": int(np.max(once_groups)),
+                 "middle_tokens": spec.budget - 2 * n, "groups_of_the_regrouped_cache": -(-(spec.budget - 2 * n) // G)})
+    return rows
+
+
 def frame_attention(torch, xsv, FrameSource, CONFIGS, reps=20):
     rows = []
     for cid in (2, 4):
@@ -162,6 +238,8 @@ def main():
     ap.add_argument("--granularity", action="store_true", help="per-token vs per-channel quantization error table")
     ap.add_argument("--frame-attention", action="store_true", help="time the frame-wise attention entry point")
     ap.add_argument("--selector-sweep", action="store_true", help="output error against an uncompressed cache per variant")
+    ap.add_argument("--requant-study", type=int, default=0, metavar="FRAMES",
+                    help="fixed points, error drift and the cost of quantizing once, over FRAMES frames of one layer")
     args = ap.parse_args()
 
     import torch
@@ -194,6 +272,10 @@ def main():
 
     if args.selector_sweep:
         for r in selector_sweep(torch, xsv, FrameSource, CONFIGS):
+            print(json.dumps(r), flush=True)
+
+    if args.requant_study:
+        for r in requant_study(torch, xsv, FrameSource, CONFIGS, args.requant_study):
             print(json.dumps(r), flush=True)
 
     if args.long:
