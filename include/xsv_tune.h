@@ -24,7 +24,7 @@ int xsv_set_attend_splits(xsv_ctx* ctx, int per_layer_calls, int batched_calls);
  * is long (more than about 24 key tiles per workgroup).  Ignored when overlap is off or splits are fixed. */
 int xsv_set_side_cus(xsv_ctx* ctx, int compute_units);
 /* Tuning: in xsv_step / xsv_step_all_layers with overlap, cut every (head, query block) into one more key
- * range than the spare units allow, the extra one `percent` of a full range long (1..100, default 50; 0 = off): its
+ * range than the spare units allow, the extra one `percent` of a full range long (1..100; 0 = off; -1 = default: 35, or 50 in overlap mode 2): its
  * workgroups end early and hand their compute units to the chain for the rest of the attention launch. */
 int xsv_set_short_range(xsv_ctx* ctx, int percent);
 /* Tuning: what a key tile of the frame's own bf16 rows costs the attention kernel relative to a tile of the packed

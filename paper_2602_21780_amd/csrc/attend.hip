@@ -23,6 +23,7 @@
 //   piece may end one unit and begin the next; it handles them one after the other.  A unit
 //   covered by one piece is normalized and written directly; otherwise each piece writes
 //   unnormalized partials that combine_kernel merges.
+#include <cstddef>
 #include <type_traits>
 
 #include "xsv_internal.h"
@@ -338,14 +339,31 @@ struct Partition {
 };
 
 // ---- the kernel ----------------------------------------------------------------------------------
-template <int BITS, int G, int NW, int QB>
+// ONE_LAYER: the launch works on a single layer (the per-layer calls).  The layer index is then a constant, so every
+// pointer of the launch can be fetched from the kernel arguments right at the start, in one round trip, instead of
+// after the workgroup has worked out which layer its piece belongs to.
+template <int BITS, int G, int NW, int QB, bool ONE_LAYER>
 __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
   constexpr int NT = NW * 64, NH = NT / 2;
   constexpr int kRowsWG = 32 * QB * NW;  // query rows per workgroup
+  {
+    // The argument block is read field by field further down, each read a scalar load the next instructions wait
+    // for, and at the start of a launch every one of them misses the scalar cache: several memory round trips in a
+    // row before a workgroup can ask for its first tile.  One load from every 64-byte line the kernel will touch
+    // (the fields behind the layer table, and the first layer's pointers), all issued here and waited for once,
+    // brings those lines in together.
+#if defined(__HIP_DEVICE_COMPILE__)  // (the builtin exists in the device pass only)
+    const uint32_t* args = static_cast<const uint32_t*>(__builtin_amdgcn_kernarg_segment_ptr());
+    constexpr unsigned kFirst = offsetof(AttendArgs, n_layers) / 4, kLast = (sizeof(AttendArgs) - 4) / 4;
+    const uint32_t w0 = args[0], w1 = args[16], w2 = args[kFirst], w3 = args[kFirst + 16], w4 = args[kFirst + 32],
+                   w5 = args[kLast];
+    asm volatile("" ::"s"(w0), "s"(w1), "s"(w2), "s"(w3), "s"(w4), "s"(w5));
+#endif
+  }
   __shared__ __attribute__((aligned(16))) uint16_t lds_k[2][kLdsTile];
   __shared__ __attribute__((aligned(16))) uint16_t lds_v[2][kLdsTile];
 
-  const int H = a.pool.H, n = a.n, Tc = a.Tc;
+  const int H = a.H, n = a.n, Tc = a.Tc;
   const int nqb = (n + kRowsWG - 1) / kRowsWG;
   // the wave index as a scalar the compiler knows to be the same for all lanes: what depends on it - the staging
   // role and every pointer chosen by it - lives in scalar registers, and the role's branches are scalar branches
@@ -359,57 +377,80 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
 
   // tiles of a unit: cache blocks, then the frame's own tokens (each range padded to 64 on its own)
   const int n_ct = (Tc + kTile - 1) / kTile, n_ft = (n + kTile - 1) / kTile;
-  const Partition part{(long long)a.b.n_layers * H * nqb * (n_ct + n_ft), n_ct + n_ft, (int)gridDim.x};
+  const Partition part{(long long)a.n_layers * H * nqb * (n_ct + n_ft), n_ct + n_ft, (int)gridDim.x};
   // Logical workgroup.  Workgroups whose blockIdx agree modulo 8 run on the same XCD and share its L2;
   // when every unit is cut into the same number of key ranges, the query blocks of one (layer, head,
-  // key range) — which read the same K/V tiles — are placed on one XCD.
+  // key range) - which read the same K/V tiles - are placed on one XCD.
+  // (Every integer division by a launch parameter is some thirty instructions here, and a workgroup's first tile
+  // waits behind all of them: where the quotients are already at hand they are kept - `fast` below - instead of
+  // being derived again from the logical index.)
   int wg = blockIdx.x;
+  bool fast = false;      // this workgroup's (unit, range, query block, head) are known without further divisions
+  int f_unit = 0, f_range = 0, f_qb = 0, f_head = 0;
   if (a.xcd_ranges > 0) {
     const int xcd = wg & 7, slot = wg >> 3;
-    const int g = (slot / nqb) * 8 + xcd;  // (layer, head, key range) triple
-    wg = ((g / a.xcd_ranges) * nqb + slot % nqb) * a.xcd_ranges + g % a.xcd_ranges;
+    const int sq = slot / nqb, sr = slot - sq * nqb;
+    const int g = sq * 8 + xcd;  // (layer, head, key range) triple
+    const int gq = g / a.xcd_ranges, gr = g - gq * a.xcd_ranges;
+    wg = (gq * nqb + sr) * a.xcd_ranges + gr;
+    if (a.equal_ranges == a.xcd_ranges) {  // unit = wg / ranges, range = wg % ranges
+      fast = true;
+      f_unit = gq * nqb + sr;
+      f_range = gr;
+      f_qb = sr;      // unit % nqb
+      f_head = gq;    // unit / nqb: (layer, head); the head itself when the launch has one layer
+    }
   }
   // this workgroup's piece [piece_first, piece_end) of the (unit, tile) line: an equal share of the line, or - when
   // every unit is cut into the same ranges - range wg % R of unit wg / R from the host's table of range starts
   // (read with constant indices: a dynamically indexed kernel argument would be copied to scratch memory)
   long long piece_first, piece_end;
+  int my_range = 0;  // which of its unit's key ranges this workgroup holds (equal ranges only)
   if (a.equal_ranges <= 0) {
     piece_first = part.begin(wg);
     piece_end = part.begin(wg + 1);
   } else {
-    const int un = wg / a.equal_ranges, p = wg % a.equal_ranges;
+    const int un = fast ? f_unit : wg / a.equal_ranges;
+    my_range = fast ? f_range : wg - un * a.equal_ranges;
     int b0 = 0, b1 = 0;
 #pragma unroll
     for (int i = 0; i < kMaxPieces; ++i) {
-      if (i == p) { b0 = a.range_begin[i]; b1 = a.range_begin[i + 1]; }
+      if (i == my_range) { b0 = a.range_begin[i]; b1 = a.range_begin[i + 1]; }
     }
     piece_first = (long long)un * part.n_tiles + b0;
     piece_end = (long long)un * part.n_tiles + b1;
+    if (!fast) f_unit = un;
   }
 
   for (long long pos = piece_first; pos < piece_end;) {
-  const int unit = part.unit_of(pos);
+  // with equal ranges a piece lies inside one unit
+  const int unit = a.equal_ranges > 0 ? f_unit : part.unit_of(pos);
   const int t_begin = (int)(pos - (long long)unit * part.n_tiles);
   const int t_end = (int)min((long long)part.n_tiles, t_begin + (piece_end - pos));
   pos += t_end - t_begin;
-  const int qb = unit % nqb, h = (unit / nqb) % H, lb = unit / (nqb * H);
+  int qb, h, lb;
+  if (fast && ONE_LAYER) {
+    qb = f_qb; h = f_head; lb = 0;
+  } else {
+    qb = unit % nqb;
+    const int lh = unit / nqb;
+    lb = ONE_LAYER ? 0 : lh / H;
+    h = lh - lb * H;
+  }
   const bool whole = t_begin == 0 && t_end == part.n_tiles;
   const int c_begin = min(t_begin, n_ct), c_end = min(t_end, n_ct);
   const int f_begin = max(t_begin, n_ct) - n_ct, f_end = max(t_end, n_ct) - n_ct;
 
-  const LayerCache lc = layer_cache(a.pool, a.b.src_buf(lb), a.b.layer0 + lb);
-  const uint16_t* qh = a.b.q[lb] + (size_t)h * a.b.q_sh;
+  const AttendLayer& ly = a.layer[lb];
+  const uint16_t* qh = ly.q + (size_t)h * a.q_sh;
   RolePtrs rp;
-  {
-    const size_t head_rows = (size_t)h * a.pool.Tcap;
-    rp.is_v = is_v;
-    rp.codes = reinterpret_cast<const uint32_t*>(is_v ? lc.vc : lc.kc) + head_rows * (kD * BITS / 32);
-    rp.ps = is_v ? lc.vs + head_rows * (kD / G) : lc.ks + (size_t)h * (a.pool.Tcap / G) * kD;
-    rp.pz = is_v ? lc.vz + head_rows * (kD / G) : lc.kz + (size_t)h * (a.pool.Tcap / G) * kD;
-    rp.lds = is_v ? lds_v[0] : lds_k[0];
-  }
-  const uint16_t* xh = is_v ? a.b.v[lb] + (size_t)h * a.b.v_sh : a.b.k[lb] + (size_t)h * a.b.k_sh;
-  const int64_t x_st = is_v ? a.b.v_st : a.b.k_st;
+  rp.is_v = is_v;
+  rp.codes = (is_v ? ly.vc : ly.kc) + (size_t)h * a.code_head;
+  rp.ps = is_v ? ly.vs + (size_t)h * a.vparam_head : ly.ks + (size_t)h * a.kparam_head;
+  rp.pz = is_v ? ly.vz + (size_t)h * a.vparam_head : ly.kz + (size_t)h * a.kparam_head;
+  rp.lds = is_v ? lds_v[0] : lds_k[0];
+  const uint16_t* xh = is_v ? ly.v + (size_t)h * a.v_sh : ly.k + (size_t)h * a.k_sh;
+  const int64_t x_st = is_v ? a.v_st : a.k_st;
 
   // query fragments (B operand): lane holds channels 16*ks + 8*hh .. +8 of its query row, as given
   // (the softmax scale is applied to the fp32 logits, so no extra bf16 rounding enters)
@@ -418,7 +459,7 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
 #pragma unroll
   for (int cb = 0; cb < QB; ++cb) {
     const int q_row = q_row0 + 32 * cb + j;
-    const uint16_t* qp = qh + (size_t)min(q_row, n - 1) * a.b.q_st;
+    const uint16_t* qp = qh + (size_t)min(q_row, n - 1) * a.q_st;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks)
       qf[cb][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qp + 16 * ks + 8 * hh));
@@ -613,16 +654,18 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
   // Phase 1: this range's tiles of the packed cache; phase 2: its tiles of the frame.  Each phase is
   // software pipelined on its own: a tile is fetched into registers while an earlier one is
   // computed, then converted into a free LDS buffer.
-  __syncthreads();  // the previous unit's last tile has been read by everybody
+  // the previous unit's last tile has been read by everybody (a workgroup's first unit has nothing to wait for, and a
+  // barrier there would only make its waves wait for the last of them to be started)
+  if (pos - (t_end - t_begin) != piece_first) __syncthreads();
   int cur = 0;      // two LDS buffers, one barrier per tile
   if (c_begin < c_end) {
     Stage<BITS, G, NH> st;
-    fetch_cache_tile<BITS, G, NH>(st, rp, a.pool.Tcap, c_begin, u);
+    fetch_cache_tile<BITS, G, NH>(st, rp, a.Tcap, c_begin, u);
     store_cache_tile<BITS, G, NH>(st, rp.lds + cur * kLdsTile, u);
     no_loads_in_flight();
     for (int t = c_begin; t < c_end; ++t) {
       __syncthreads();  // tile t is in lds[cur]; everybody is done reading lds[cur^1]
-      if (t + 1 < c_end) fetch_cache_tile<BITS, G, NH>(st, rp, a.pool.Tcap, t + 1, u);
+      if (t + 1 < c_end) fetch_cache_tile<BITS, G, NH>(st, rp, a.Tcap, t + 1, u);
       compute(cur, min(kTile, Tc - t * kTile));
       if (t + 1 < c_end) store_cache_tile<BITS, G, NH>(st, rp.lds + (cur ^ 1) * kLdsTile, u);
       no_loads_in_flight();
@@ -653,7 +696,7 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
     if (q_row >= n) continue;  // (both lanes of a row leave together, so the lane exchange below stays paired)
     if (whole) {
       const float inv = 1.0f / lsum;
-      uint16_t* op = a.b.out[lb] + ((size_t)h * n + q_row) * kD;
+      uint16_t* op = ly.out + ((size_t)h * n + q_row) * kD;
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
         const int c = 8 * q4 + 4 * hh;
@@ -668,10 +711,10 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
       // fp32).  Lane (j, hh) owns 32 channels of row j, in register order o0[0..15], o1[0..15], as
       // four 16-byte pieces i; a block of 32 rows is stored [i][hh][j], so that every store
       // instruction of the wave covers 1 KB of consecutive memory.
-      const int piece = a.equal_ranges > 0 ? wg % a.equal_ranges : wg - part.first_wg(unit);
+      const int piece = a.equal_ranges > 0 ? my_range : wg - part.first_wg(unit);
       const int nblk = (n + 31) / 32;
-      const size_t row = (((size_t)piece * a.b.n_layers + lb) * H + h) * n + q_row;
-      const size_t blk = (((size_t)piece * a.b.n_layers + lb) * H + h) * nblk + (q_row >> 5);
+      const size_t row = (((size_t)piece * a.n_layers + lb) * H + h) * n + q_row;
+      const size_t blk = (((size_t)piece * a.n_layers + lb) * H + h) * nblk + (q_row >> 5);
       float amax = 0.f;
 #pragma unroll
       for (int r = 0; r < 16; ++r) amax = fmaxf(amax, fmaxf(fabsf(o0[cb][r]), fabsf(o1[cb][r])));
@@ -683,11 +726,11 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
         hw[r >> 1] = pack_f16(__builtin_amdgcn_ldexpf(o0[cb][r], -e), __builtin_amdgcn_ldexpf(o0[cb][r + 1], -e));
         hw[8 + (r >> 1)] = pack_f16(__builtin_amdgcn_ldexpf(o1[cb][r], -e), __builtin_amdgcn_ldexpf(o1[cb][r + 1], -e));
       }
-      uint4* op = reinterpret_cast<uint4*>(a.ws.attn_o) + blk * 256 + hh * 32 + j;
+      uint4* op = reinterpret_cast<uint4*>(a.attn_o) + blk * 256 + hh * 32 + j;
 #pragma unroll
       for (int i = 0; i < 4; ++i) op[i * 64] = make_uint4(hw[4 * i], hw[4 * i + 1], hw[4 * i + 2], hw[4 * i + 3]);
       if (hh == 0)
-        *reinterpret_cast<float4*>(a.ws.attn_ml + row * 4) = make_float4(-mc[cb], lsum, __builtin_amdgcn_ldexpf(1.0f, e), 0.f);
+        *reinterpret_cast<float4*>(a.attn_ml + row * 4) = make_float4(-mc[cb], lsum, __builtin_amdgcn_ldexpf(1.0f, e), 0.f);
     }
   }
   }  // units of this workgroup's piece
@@ -703,10 +746,10 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
 // a unit's edge has nothing to merge.
 // Thread = (row, lane half hh, quarter of the lane's 32 values): 8 fp16 values of every piece.
 __global__ __launch_bounds__(256) void combine_kernel(const AttendArgs a) {
-  const int H = a.pool.H, n = a.n;
+  const int H = a.H, n = a.n;
   const int nqb = (n + a.rows_wg - 1) / a.rows_wg;
   const int n_tiles = (a.Tc + kTile - 1) / kTile + (n + kTile - 1) / kTile;
-  const Partition part{(long long)a.b.n_layers * H * nqb * n_tiles, n_tiles, a.n_wgs};
+  const Partition part{(long long)a.n_layers * H * nqb * n_tiles, n_tiles, a.n_wgs};
   int unit, S;
   if (a.equal_ranges > 0) {  // every unit is cut into the same number of ranges: x = unit
     unit = blockIdx.x;
@@ -726,14 +769,14 @@ __global__ __launch_bounds__(256) void combine_kernel(const AttendArgs a) {
   const int q_row = qb * a.rows_wg + 32 * blockIdx.y + jrow;
   if (q_row >= n) return;
   const int nblk = (n + 31) / 32;
-  const size_t rows = (size_t)a.b.n_layers * H * n, blks = (size_t)a.b.n_layers * H * nblk;
+  const size_t rows = (size_t)a.n_layers * H * n, blks = (size_t)a.n_layers * H * nblk;
   const size_t row = ((size_t)lb * H + h) * n + q_row;
   const size_t blk = ((size_t)lb * H + h) * nblk + (q_row >> 5);
   float ms[kMaxPieces], ls[kMaxPieces], sc[kMaxPieces];
   float M = kNegBig;
 #pragma unroll 4
   for (int s = 0; s < S; ++s) {
-    const float4 ml = *reinterpret_cast<const float4*>(a.ws.attn_ml + (s * rows + row) * 4);
+    const float4 ml = *reinterpret_cast<const float4*>(a.attn_ml + (s * rows + row) * 4);
     ms[s] = ml.x;
     ls[s] = ml.y;
     sc[s] = ml.z;
@@ -743,7 +786,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const AttendArgs a) {
 #pragma unroll 4
   for (int s = 0; s < S; ++s) {
     const float wgt = __builtin_amdgcn_exp2f(ms[s] - M);
-    const uint4 o = reinterpret_cast<const uint4*>(a.ws.attn_o)[(s * blks + blk) * 256 + qd * 64 + hh * 32 + jrow];
+    const uint4 o = reinterpret_cast<const uint4*>(a.attn_o)[(s * blks + blk) * 256 + qd * 64 + hh * 32 + jrow];
     L += wgt * ls[s];
     const float ws = wgt * sc[s];
     const uint32_t ow[4] = {o.x, o.y, o.z, o.w};
@@ -757,19 +800,20 @@ __global__ __launch_bounds__(256) void combine_kernel(const AttendArgs a) {
   const float inv = 1.0f / L;
   // values 8*qd + t of the lane: accumulator registers r = 8*(qd%2) + t of o0 (qd < 2) or o1, i.e.
   // channels 32*(qd/2) + 16*(qd%2) + {0, 8} + 4*hh + 0..3
-  uint16_t* op = a.b.out[lb] + ((size_t)h * n + q_row) * kD + 32 * (qd >> 1) + 16 * (qd & 1) + 4 * hh;
+  uint16_t* op = a.layer[lb].out + ((size_t)h * n + q_row) * kD + 32 * (qd >> 1) + 16 * (qd & 1) + 4 * hh;
   *reinterpret_cast<uint2*>(op) = make_uint2(pack_bf16(acc[0] * inv, acc[1] * inv), pack_bf16(acc[2] * inv, acc[3] * inv));
   *reinterpret_cast<uint2*>(op + 8) = make_uint2(pack_bf16(acc[4] * inv, acc[5] * inv), pack_bf16(acc[6] * inv, acc[7] * inv));
 }
 
 template <int BITS, int G, int NW, int QB>
 static hipError_t launch_attend_t(const AttendArgs& a, hipStream_t stream, hipEvent_t between) {
-  hipLaunchKernelGGL((attend_kernel<BITS, G, NW, QB>), dim3(a.n_wgs), dim3(NW * 64), 0, stream, a);
+  if (a.n_layers == 1) hipLaunchKernelGGL((attend_kernel<BITS, G, NW, QB, true>), dim3(a.n_wgs), dim3(NW * 64), 0, stream, a);
+  else hipLaunchKernelGGL((attend_kernel<BITS, G, NW, QB, false>), dim3(a.n_wgs), dim3(NW * 64), 0, stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (between && (e = hipEventRecord(between, stream)) != hipSuccess) return e;
   if (a.cut) {
-    const int n_units = a.b.n_layers * a.pool.H * ((a.n + a.rows_wg - 1) / a.rows_wg);
+    const int n_units = a.n_layers * a.H * ((a.n + a.rows_wg - 1) / a.rows_wg);
     hipLaunchKernelGGL(combine_kernel, dim3(a.equal_ranges > 0 ? n_units : a.n_wgs - 1, (a.rows_wg + 31) / 32), dim3(256), 0,
                        stream, a);
     e = hipGetLastError();
@@ -817,7 +861,7 @@ AttendPlan plan_attend(int variant, int n_layers, int H, int n, int Tc, int want
 }
 
 hipError_t launch_attend(const AttendArgs& a, hipStream_t stream, hipEvent_t between) {
-  const int bits = a.pool.bits, G = a.pool.G;
+  const int bits = a.bits, G = a.G;
   if (bits == 16) return launch_attend_v<16, 64>(a, stream, between);
   if (bits == 4 && G == 64) return launch_attend_v<4, 64>(a, stream, between);
   if (bits == 4 && G == 32) return launch_attend_v<4, 32>(a, stream, between);

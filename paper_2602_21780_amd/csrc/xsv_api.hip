@@ -69,7 +69,7 @@ struct xsv_ctx {
   std::vector<hipEvent_t> chain_events;  // triples on the chain's stream: before score, after select, after re-quantize
   size_t chain_used = 0;
   int frame_tile_cost = 95;  // cost of a key tile of the frame's own rows in percent of a cache tile's (attention range cut)
-  int short_pct = 50; // xsv_step: length of one extra, short key range per unit, in percent of a long one (0 = none)
+  int short_pct = -1; // xsv_step: length of one extra, short key range per unit, in percent of a long one (0 = none, -1 = by overlap mode)
   int side_cus = -1;  // compute units xsv_step leaves to the prune chain while attention runs (-1: by launch size)
   size_t part_rows = 0;  // rows the partial-output workspace holds
   int n_cu = 256;
@@ -266,17 +266,35 @@ void range_starts(int n_ct, int n_ft, int R, int last_pct, int frame_cost, int32
 int do_attend(xsv_ctx* ctx, int layer0, int n_layers, const xsv_tensor* q, const xsv_tensor* k, const xsv_tensor* v,
               void* const* out, int splits_req, int spare_cus, bool frame_only = false) {
   AttendArgs a{};
-  int rc = fill_batch(ctx, a.b, layer0, n_layers, q, k, v, out);
-  if (rc != XSV_OK) return rc;
-  a.pool = ctx->pool;
-  a.ws = ctx->ws;
+  {
+    Batch b;
+    int rc = fill_batch(ctx, b, layer0, n_layers, q, k, v, out);
+    if (rc != XSV_OK) return rc;
+    const CachePool& p = ctx->pool;
+    for (int i = 0; i < n_layers; ++i) {
+      const LayerCache lc = layer_cache(p, b.src_buf(i), layer0 + i);
+      AttendLayer& ly = a.layer[i];
+      ly.kc = reinterpret_cast<const uint32_t*>(lc.kc); ly.ks = lc.ks; ly.kz = lc.kz;
+      ly.vc = reinterpret_cast<const uint32_t*>(lc.vc); ly.vs = lc.vs; ly.vz = lc.vz;
+      ly.q = b.q[i]; ly.k = b.k[i]; ly.v = b.v[i]; ly.out = b.out[i];
+    }
+    a.n_layers = n_layers; a.H = p.H; a.bits = p.bits; a.G = p.G; a.Tcap = p.Tcap;
+    a.code_head = (uint32_t)((size_t)p.Tcap * (kD * p.bits / 32));
+    a.kparam_head = (uint32_t)((size_t)(p.Tcap / p.G) * kD);
+    a.vparam_head = (uint32_t)((size_t)p.Tcap * (kD / p.G));
+    a.q_sh = b.q_sh; a.q_st = b.q_st; a.k_sh = b.k_sh; a.k_st = b.k_st; a.v_sh = b.v_sh; a.v_st = b.v_st;
+    a.attn_o = ctx->ws.attn_o; a.attn_ml = ctx->ws.attn_ml;
+  }
   a.Tc = frame_only ? 0 : ctx->layers[layer0].T;
   a.n = ctx->cfg.tokens_per_frame;
   a.variant = ctx->attend_variant;
   AttendPlan plan = choose_grid(ctx, n_layers, a.Tc, splits_req, spare_cus);
   const int n_ct = (a.Tc + kTile - 1) / kTile, n_ft = (a.n + kTile - 1) / kTile, n_tiles = n_ct + n_ft;
   bool short_last = false;
-  if (splits_req <= 0 && spare_cus > 0 && ctx->short_pct > 0) {
+  // with deferred joins the chain only has to keep up, so the short range can be longer (the long ones shorter) than
+  // when every step waits for its chain before it returns
+  const int short_pct = ctx->short_pct >= 0 ? ctx->short_pct : (ctx->overlap == 2 ? 50 : 35);
+  if (splits_req <= 0 && spare_cus > 0 && short_pct > 0) {
     // beside the overlapped chain: the equal cut that leaves spare units, plus one short range per unit
     const int rows = attend_rows_per_workgroup(ctx->attend_variant);
     const int n_units = ((a.n + rows - 1) / rows) * ctx->cfg.n_heads * n_layers;
@@ -297,7 +315,7 @@ int do_attend(xsv_ctx* ctx, int layer0, int n_layers, const xsv_tensor* q, const
     const int ranges = plan.n_wgs % n_units == 0 ? plan.n_wgs / n_units : 0;
     a.equal_ranges = (ranges > 1 && ranges <= kMaxPieces && ranges <= n_tiles) ? ranges : 0;
     a.xcd_ranges = (ranges > 0 && (ctx->cfg.n_heads * n_layers * ranges) % 8 == 0) ? ranges : 0;
-    if (a.equal_ranges > 0) range_starts(n_ct, n_ft, a.equal_ranges, short_last ? ctx->short_pct : 100, ctx->frame_tile_cost, a.range_begin);
+    if (a.equal_ranges > 0) range_starts(n_ct, n_ft, a.equal_ranges, short_last ? short_pct : 100, ctx->frame_tile_cost, a.range_begin);
   }
   ctx->last_attend_wgs = plan.n_wgs;
   a.qscale = ctx->cfg.softmax_scale * 1.4426950408889634f;
@@ -629,7 +647,7 @@ int xsv_last_attend_workgroups(xsv_ctx* ctx, int32_t* workgroups) {
 }
 
 int xsv_set_short_range(xsv_ctx* ctx, int percent) {
-  if (!ctx || percent < 0 || percent > 100) return XSV_ERR_ARG;
+  if (!ctx || percent < -1 || percent > 100) return XSV_ERR_ARG;
   ctx->short_pct = percent;
   return XSV_OK;
 }

@@ -110,10 +110,29 @@ struct Workspace {
 // ---- launchers (defined in the .hip files; every one only enqueues on `stream`) -----------------
 
 constexpr int kMaxPieces = 16;  // workgroups that may share one unit
+// One layer of an attention launch: device pointers at head 0 of the buffer that holds the layer's cache, and of the
+// frame's tensors.  (Resolved on the host: a workgroup's first tile waits behind whatever address arithmetic the
+// kernel has to do, and the argument block stays small.)
+struct AttendLayer {
+  const uint32_t* kc;
+  const float* ks;
+  const float* kz;
+  const uint32_t* vc;
+  const float* vs;
+  const float* vz;
+  const uint16_t* q;
+  const uint16_t* k;
+  const uint16_t* v;
+  uint16_t* out;
+};
 struct AttendArgs {
-  CachePool pool;
-  Batch b;
-  Workspace ws;
+  AttendLayer layer[kMaxBatch];
+  int n_layers, H, bits, G;
+  int Tcap;
+  uint32_t code_head, kparam_head, vparam_head;  // elements (dwords / floats) between two heads of kc|vc, ks|kz, vs|vz
+  int64_t q_sh, q_st, k_sh, k_st, v_sh, v_st;    // strides of the frame tensors in elements
+  uint16_t* attn_o;  // partial outputs of cut units, see Workspace
+  float* attn_ml;
   int Tc, n;
   int variant;   // waves x query rows per wave of a workgroup: 0: 4 x 64, 1: 4 x 32, 2: 8 x 32, 3: 8 x 64
   int n_wgs;     // workgroups the (unit, tile) line is cut into (from plan_attend)
