@@ -59,9 +59,11 @@ typedef struct {
 } xsv_config;
 
 typedef struct {
-  const void* ptr;      /* DEVICE, bf16 */
-  int64_t stride_head;  /* elements */
-  int64_t stride_token; /* elements, >= head_dim */
+  const void* ptr;      /* DEVICE, bf16, 16-byte aligned */
+  int64_t stride_head;  /* elements, >= 0, a multiple of 8 */
+  int64_t stride_token; /* elements, a multiple of 8, >= head_dim and <= 2^24 (rows are fetched
+                           in 16-byte pieces through 32-bit buffer offsets); anything else is
+                           XSV_ERR_ARG */
 } xsv_tensor;
 
 /* ---- life cycle ------------------------------------------------------------------------------- */
@@ -109,7 +111,11 @@ int xsv_score_prune(xsv_ctx* ctx, int layer, xsv_tensor q);
  *   code = clamp(round(x / s) + zero, 0, 2^b - 1),   round = nearest-even, x / s the IEEE fp32 quotient,
  * keys per (head, channel) over groups of G consecutive kept tokens (short last group on its own),
  * values per (head, token) over groups of G consecutive channels.  With kv_bits == 16 the rows are
- * stored as bf16 unchanged.  Swaps the layer's cache buffers; cache length becomes the keep length. */
+ * stored as bf16 unchanged.  The result is the layer's cache; cache length becomes the keep length.
+ * (A budgeted cache is written into the layer's second buffer and the two swap; a cache with
+ * budget 0 never moves a row and is rewritten in place in its single buffer.  A block of 64 cached
+ * tokens that keeps its place and that one re-quantization reproduced bit for bit is not
+ * recomputed again - its result is the same bytes either way.) */
 int xsv_quantize(xsv_ctx* ctx, int layer, xsv_tensor k_new, xsv_tensor v_new);
 
 /* The three calls above for one layer.  Attention runs on the context's stream while score, select

@@ -17,12 +17,21 @@
 //   same code on mirrored layouts).  LDS is double buffered; the next tile's packed codes and
 //   group parameters are fetched into registers before the current tile's MFMAs are issued.
 //   Partition.  A unit is one (layer, head, block of NW*QB*32 query rows); its work is its key tiles.
-//   All units' tiles form one line of n_units * n_tiles items, cut into gridDim.x equal pieces, one
-//   per workgroup — so any number of workgroups (a full chip, or a chip minus the compute units
-//   left to the kernels that run beside this one) gets the same amount of work.  A workgroup's
-//   piece may end one unit and begin the next; it handles them one after the other.  A unit
-//   covered by one piece is normalized and written directly; otherwise each piece writes
-//   unnormalized partials that combine_kernel merges.
+//   Two forms, chosen by the host.  (a) Every unit is cut into the same number R of key ranges
+//   (gridDim.x = units * R): the host passes where each range begins, placed so that the ranges cost
+//   the same (a tile of the frame's own rows costs a little less than a cache tile, and the last
+//   range may be made short on purpose so that its compute units are free early for the kernels
+//   that run beside this one); the grid is permuted so that the query blocks of one (layer, head,
+//   range), which read the same tiles, run on one XCD and share its L2.  (b) Otherwise all units'
+//   tiles form one line of n_units * n_tiles items cut into gridDim.x equal pieces, so that any
+//   number of workgroups gets the same amount of work; a piece may end one unit and begin the
+//   next, and the workgroup handles them one after the other.  In both forms a unit covered by one
+//   workgroup is normalized and written directly; otherwise each workgroup writes an unnormalized
+//   partial that combine_kernel merges.
+//   Softmax.  No row maximum on the common path: the reference of the exponent only moves when a
+//   row sum leaves [0, 2^64] (which also catches the very first tile, whose reference is a
+//   sentinel that sends every probability to +infinity); then, and only then, the maximum is
+//   taken, the accumulators are rescaled and the block's probabilities are recomputed.
 #include <cstddef>
 #include <type_traits>
 

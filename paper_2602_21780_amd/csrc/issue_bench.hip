@@ -1,6 +1,6 @@
 // Issue-rate microbenchmarks for gfx950: what one SIMD of a compute unit can issue per cycle for the instruction
 // kinds of the attention kernel's inner loop (fp32 multiply-add, exponential, bf16 pack, bf16 dot product, the
-// 32x32x16 bf16 MFMA, and mixtures), with one and with two waves per SIMD.  A standalone program:
+// 32x32x16 bf16 MFMA, and mixtures), with one to four waves per SIMD.  A standalone program:
 //   python -m paper_2602_21780_amd.build      (builds paper_2602_21780_amd/issue_bench beside the library)
 //   ./paper_2602_21780_amd/issue_bench
 // Every workgroup runs the same straight-line loop; wave 0 of workgroup 0 reports its cycle counter (s_memtime),
@@ -20,7 +20,7 @@ typedef __attribute__((ext_vector_type(2))) float f32x2;
 __device__ __forceinline__ unsigned long long now() { return __builtin_amdgcn_s_memtime(); }
 
 template <int MODE>
-__global__ __launch_bounds__(512) void k(unsigned long long* out, float* sink, int iters) {
+__global__ __launch_bounds__(1024) void k(unsigned long long* out, float* sink, int iters) {
   float a0 = threadIdx.x, a1 = a0 + 1, a2 = a0 + 2, a3 = a0 + 3, a4 = a0 * .5f, a5 = a0 * .25f, a6 = a0 * .125f, a7 = 7.f;
   const float c = 1.0001f, d = 0.0001f;
   f32x16 acc0 = {0}, acc1 = {0}, acc2 = {0}, acc3 = {0};
@@ -88,12 +88,21 @@ __global__ __launch_bounds__(512) void k(unsigned long long* out, float* sink, i
            asm volatile("v_exp_f32 %0, %0\n v_exp_f32 %1, %1\n v_exp_f32 %2, %2\n v_exp_f32 %3, %3\n" : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3));
            acc3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc3, 0, 0, 0);
            asm volatile("v_exp_f32 %0, %0\n v_exp_f32 %1, %1\n v_exp_f32 %2, %2\n v_exp_f32 %3, %3\n" : "+v"(a4), "+v"(a5), "+v"(a6), "+v"(a7));)
+    } else if constexpr (MODE == 10) {  // the attention loop's mix per 16 MFMAs: 96 fma + 32 exp, spread evenly
+      REP4(acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc0, 0, 0, 0);
+           asm volatile("v_fma_f32 %0, %0, %4, %5\n v_fma_f32 %1, %1, %4, %5\n v_fma_f32 %2, %2, %4, %5\n v_exp_f32 %3, %3\n v_fma_f32 %0, %0, %4, %5\n v_fma_f32 %1, %1, %4, %5\n v_fma_f32 %2, %2, %4, %5\n v_exp_f32 %3, %3\n" : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3) : "v"(c), "v"(d));
+           acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc1, 0, 0, 0);
+           asm volatile("v_fma_f32 %0, %0, %4, %5\n v_fma_f32 %1, %1, %4, %5\n v_fma_f32 %2, %2, %4, %5\n v_exp_f32 %3, %3\n v_fma_f32 %0, %0, %4, %5\n v_fma_f32 %1, %1, %4, %5\n v_fma_f32 %2, %2, %4, %5\n v_exp_f32 %3, %3\n" : "+v"(a4), "+v"(a5), "+v"(a6), "+v"(a7) : "v"(c), "v"(d));
+           acc2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc2, 0, 0, 0);
+           asm volatile("v_fma_f32 %0, %0, %4, %5\n v_fma_f32 %1, %1, %4, %5\n v_fma_f32 %2, %2, %4, %5\n v_exp_f32 %3, %3\n v_fma_f32 %0, %0, %4, %5\n v_fma_f32 %1, %1, %4, %5\n v_fma_f32 %2, %2, %4, %5\n v_exp_f32 %3, %3\n" : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3) : "v"(c), "v"(d));
+           acc3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc3, 0, 0, 0);
+           asm volatile("v_fma_f32 %0, %0, %4, %5\n v_fma_f32 %1, %1, %4, %5\n v_fma_f32 %2, %2, %4, %5\n v_exp_f32 %3, %3\n v_fma_f32 %0, %0, %4, %5\n v_fma_f32 %1, %1, %4, %5\n v_fma_f32 %2, %2, %4, %5\n v_exp_f32 %3, %3\n" : "+v"(a4), "+v"(a5), "+v"(a6), "+v"(a7) : "v"(c), "v"(d));)
     } else if constexpr (MODE == 9) {  // 16 dependent mfma (one accumulator)
       REP16(acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc0, 0, 0, 0);)
     }
   }
   const unsigned long long t1 = now();
-  if ((threadIdx.x & 63) == 0) out[blockIdx.x * 8 + (threadIdx.x >> 6)] = t1 - t0;
+  if ((threadIdx.x & 63) == 0) out[blockIdx.x * 16 + (threadIdx.x >> 6)] = t1 - t0;
   sink[blockIdx.x * blockDim.x + threadIdx.x] = a0 + a1 + a2 + a3 + a4 + a5 + a6 + a7 + acc0[0] + acc1[1] + acc2[2] + acc3[3];
 }
 
@@ -110,7 +119,7 @@ void run(const char* name, int per_iter, int threads, unsigned long long* dout, 
   (void)hipDeviceSynchronize();
   float ms = 0.f;
   (void)hipEventElapsedTime(&ms, e0, e1);
-  std::vector<unsigned long long> h(blocks * 8);
+  std::vector<unsigned long long> h(blocks * 16);
   if (hipMemcpy(h.data(), dout, h.size() * 8, hipMemcpyDeviceToHost) != hipSuccess) { printf("copy failed\n"); return; }
   double cyc = (double)h[0] / iters;
   // wall: all waves of a SIMD together; cycles: the reporting wave alone (with two waves per SIMD the older wave is
@@ -121,8 +130,8 @@ void run(const char* name, int per_iter, int threads, unsigned long long* dout, 
 
 int main() {
   unsigned long long* dout; float* sink;
-  if (hipMalloc(&dout, 256 * 8 * 8) != hipSuccess || hipMalloc(&sink, 256 * 512 * 4) != hipSuccess) { printf("no device memory\n"); return 1; }
-  for (int threads : {256, 512}) {
+  if (hipMalloc(&dout, 256 * 16 * 8) != hipSuccess || hipMalloc(&sink, 256 * 1024 * 4) != hipSuccess) { printf("no device memory\n"); return 1; }
+  for (int threads : {256, 512, 768, 1024}) {
     run<0>("64 fma (8 chains)", 64, threads, dout, sink);
     run<1>("64 exp (8 chains)", 64, threads, dout, sink);
     run<2>("64 dot2c (1 chain)", 64, threads, dout, sink);
@@ -133,6 +142,7 @@ int main() {
     run<6>("16 mfma + 64 fma interleaved", 80, threads, dout, sink);
     run<7>("16 mfma + 128 fma interleaved", 144, threads, dout, sink);
     run<8>("16 mfma + 64 exp interleaved", 80, threads, dout, sink);
+    run<10>("16 mfma + 96 fma + 32 exp", 144, threads, dout, sink);
   }
   return 0;
 }

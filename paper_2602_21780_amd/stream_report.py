@@ -228,6 +228,42 @@ def frame_attention(torch, xsv, FrameSource, CONFIGS, reps=20):
     return rows
 
 
+def attend_shapes(torch, xsv, FrameSource, CONFIGS, reps=3):
+    """Attention and merge kernel spans (library events on the launch stream, the span of an empty event pair taken
+    off) for every workgroup shape and number of key ranges per unit, at the saturated cache of the 24-layer
+    workload, one layer per launch, nothing running beside it."""
+    spec = CONFIGS[2]
+    L, n = spec.n_layers, spec.tokens_per_frame
+    src = FrameSource(spec, "cuda:0")
+    sat = spec.budget // n + 2
+    out = torch.empty((L, spec.n_heads, n, spec.head_dim), dtype=torch.bfloat16, device="cuda:0")
+    ctx = xsv.Context.from_spec(spec)
+    ctx.set_overlap(0)
+    for f in range(sat + 1):
+        q, k, v = src.frame(f)
+        ctx.step_all_layers(q, k, v, out)
+    q, k, v = src.frame(sat + 1)
+    rows = []
+    for variant, shape in ((3, "8 waves x 64 rows"), (2, "8 waves x 32 rows"), (0, "4 waves x 64 rows"), (1, "4 waves x 32 rows")):
+        ctx.set_attend_variant(variant)
+        for ranges in (0, 1, 2, 3, 4, 5, 6, 8):
+            ctx.set_attend_splits(ranges, 0)
+            ctx.set_attend_timing(True)
+            for _ in range(reps):  # the same frame again: only the time matters, and the cache stays at its saturated length
+                for l in range(L):
+                    ctx.dequant_attend(l, q[l], k[l], v[l], out[l])
+                for l in range(L):
+                    ctx.score_prune(l, q[l])
+                    ctx.quantize(l, k[l], v[l])
+            nl, a, m, e = ctx.attend_times()
+            ctx.set_attend_timing(False)
+            rows.append({"shape": shape, "key_ranges": ranges or "auto", "workgroups": ctx.last_attend_workgroups(),
+                         "attend_us": round(1e3 * (a - e), 1), "merge_us": round(1e3 * max(0.0, m - e), 1),
+                         "sum_us": round(1e3 * (a - e + max(0.0, m - e)), 1), "launches": nl})
+    ctx.destroy()
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--configs", default="", help="comma-separated workload ids of inputs.CONFIGS")
@@ -240,6 +276,8 @@ def main():
     ap.add_argument("--selector-sweep", action="store_true", help="output error against an uncompressed cache per variant")
     ap.add_argument("--requant-study", type=int, default=0, metavar="FRAMES",
                     help="fixed points, error drift and the cost of quantizing once, over FRAMES frames of one layer")
+    ap.add_argument("--attend-shapes", action="store_true",
+                    help="attention / merge time per workgroup shape and number of key ranges (24-layer workload)")
     args = ap.parse_args()
 
     import torch
@@ -268,6 +306,10 @@ def main():
 
     if args.frame_attention:
         for r in frame_attention(torch, xsv, FrameSource, CONFIGS):
+            print(json.dumps(r), flush=True)
+
+    if args.attend_shapes:
+        for r in attend_shapes(torch, xsv, FrameSource, CONFIGS):
             print(json.dumps(r), flush=True)
 
     if args.selector_sweep:
