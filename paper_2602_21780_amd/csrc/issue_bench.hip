@@ -11,6 +11,7 @@
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 
 #define REP4(x) x x x x
@@ -24,6 +25,7 @@ __global__ __launch_bounds__(1024) void k(unsigned long long* out, float* sink, 
   float a0 = threadIdx.x, a1 = a0 + 1, a2 = a0 + 2, a3 = a0 + 3, a4 = a0 * .5f, a5 = a0 * .25f, a6 = a0 * .125f, a7 = 7.f;
   const float c = 1.0001f, d = 0.0001f;
   f32x16 acc0 = {0}, acc1 = {0}, acc2 = {0}, acc3 = {0};
+  f32x4 q0 = {0}, q1 = {0}, q2 = {0}, q3 = {0};
   bf16x8 fa = {1, 1, 1, 1, 1, 1, 1, 1}, fb = fa;
   asm volatile("" : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3), "+v"(a4), "+v"(a5), "+v"(a6), "+v"(a7));
   asm volatile("" : "+v"(fa), "+v"(fb));
@@ -97,13 +99,35 @@ __global__ __launch_bounds__(1024) void k(unsigned long long* out, float* sink, 
            asm volatile("v_fma_f32 %0, %0, %4, %5\n v_fma_f32 %1, %1, %4, %5\n v_fma_f32 %2, %2, %4, %5\n v_exp_f32 %3, %3\n v_fma_f32 %0, %0, %4, %5\n v_fma_f32 %1, %1, %4, %5\n v_fma_f32 %2, %2, %4, %5\n v_exp_f32 %3, %3\n" : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3) : "v"(c), "v"(d));
            acc3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc3, 0, 0, 0);
            asm volatile("v_fma_f32 %0, %0, %4, %5\n v_fma_f32 %1, %1, %4, %5\n v_fma_f32 %2, %2, %4, %5\n v_exp_f32 %3, %3\n v_fma_f32 %0, %0, %4, %5\n v_fma_f32 %1, %1, %4, %5\n v_fma_f32 %2, %2, %4, %5\n v_exp_f32 %3, %3\n" : "+v"(a4), "+v"(a5), "+v"(a6), "+v"(a7) : "v"(c), "v"(d));)
+    } else if constexpr (MODE == 11) {  // 32 mfma 16x16x32 (the flops of 16 of the 32x32x16), 4 accumulators
+      REP4(q0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fb, q0, 0, 0, 0); q1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fb, q1, 0, 0, 0);
+           q2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fb, q2, 0, 0, 0); q3 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fb, q3, 0, 0, 0);
+           q0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fb, q0, 0, 0, 0); q1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fb, q1, 0, 0, 0);
+           q2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fb, q2, 0, 0, 0); q3 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fb, q3, 0, 0, 0);)
+    } else if constexpr (MODE == 12) {  // the same 32 mfma 16x16x32, each followed by 4 fma (= 128 fma)
+      REP4(q0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fb, q0, 0, 0, 0);
+           asm volatile("v_fma_f32 %0, %0, %4, %5\n v_fma_f32 %1, %1, %4, %5\n v_fma_f32 %2, %2, %4, %5\n v_fma_f32 %3, %3, %4, %5\n" : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3) : "v"(c), "v"(d));
+           q1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fb, q1, 0, 0, 0);
+           asm volatile("v_fma_f32 %0, %0, %4, %5\n v_fma_f32 %1, %1, %4, %5\n v_fma_f32 %2, %2, %4, %5\n v_fma_f32 %3, %3, %4, %5\n" : "+v"(a4), "+v"(a5), "+v"(a6), "+v"(a7) : "v"(c), "v"(d));
+           q2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fb, q2, 0, 0, 0);
+           asm volatile("v_fma_f32 %0, %0, %4, %5\n v_fma_f32 %1, %1, %4, %5\n v_fma_f32 %2, %2, %4, %5\n v_fma_f32 %3, %3, %4, %5\n" : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3) : "v"(c), "v"(d));
+           q3 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fb, q3, 0, 0, 0);
+           asm volatile("v_fma_f32 %0, %0, %4, %5\n v_fma_f32 %1, %1, %4, %5\n v_fma_f32 %2, %2, %4, %5\n v_fma_f32 %3, %3, %4, %5\n" : "+v"(a4), "+v"(a5), "+v"(a6), "+v"(a7) : "v"(c), "v"(d));
+           q0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fb, q0, 0, 0, 0);
+           asm volatile("v_fma_f32 %0, %0, %4, %5\n v_fma_f32 %1, %1, %4, %5\n v_fma_f32 %2, %2, %4, %5\n v_fma_f32 %3, %3, %4, %5\n" : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3) : "v"(c), "v"(d));
+           q1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fb, q1, 0, 0, 0);
+           asm volatile("v_fma_f32 %0, %0, %4, %5\n v_fma_f32 %1, %1, %4, %5\n v_fma_f32 %2, %2, %4, %5\n v_fma_f32 %3, %3, %4, %5\n" : "+v"(a4), "+v"(a5), "+v"(a6), "+v"(a7) : "v"(c), "v"(d));
+           q2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fb, q2, 0, 0, 0);
+           asm volatile("v_fma_f32 %0, %0, %4, %5\n v_fma_f32 %1, %1, %4, %5\n v_fma_f32 %2, %2, %4, %5\n v_fma_f32 %3, %3, %4, %5\n" : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3) : "v"(c), "v"(d));
+           q3 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fb, q3, 0, 0, 0);
+           asm volatile("v_fma_f32 %0, %0, %4, %5\n v_fma_f32 %1, %1, %4, %5\n v_fma_f32 %2, %2, %4, %5\n v_fma_f32 %3, %3, %4, %5\n" : "+v"(a4), "+v"(a5), "+v"(a6), "+v"(a7) : "v"(c), "v"(d));)
     } else if constexpr (MODE == 9) {  // 16 dependent mfma (one accumulator)
       REP16(acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc0, 0, 0, 0);)
     }
   }
   const unsigned long long t1 = now();
   if ((threadIdx.x & 63) == 0) out[blockIdx.x * 16 + (threadIdx.x >> 6)] = t1 - t0;
-  sink[blockIdx.x * blockDim.x + threadIdx.x] = a0 + a1 + a2 + a3 + a4 + a5 + a6 + a7 + acc0[0] + acc1[1] + acc2[2] + acc3[3];
+  sink[blockIdx.x * blockDim.x + threadIdx.x] = a0 + a1 + a2 + a3 + a4 + a5 + a6 + a7 + acc0[0] + acc1[1] + acc2[2] + acc3[3] + q0[0] + q1[1] + q2[2] + q3[3];
 }
 
 template <int MODE>
@@ -143,6 +167,8 @@ int main() {
     run<7>("16 mfma + 128 fma interleaved", 144, threads, dout, sink);
     run<8>("16 mfma + 64 exp interleaved", 80, threads, dout, sink);
     run<10>("16 mfma + 96 fma + 32 exp", 144, threads, dout, sink);
+    run<11>("32 mfma 16x16x32", 32, threads, dout, sink);
+    run<12>("32 mfma 16x16x32 + 128 fma", 160, threads, dout, sink);
   }
   return 0;
 }

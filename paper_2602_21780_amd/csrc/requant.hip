@@ -338,6 +338,8 @@ __global__ __launch_bounds__(256) void requant_kernel(const RequantArgs a) {
   if (candidate) {  // did the block reproduce itself?  (bf16 rows always do: they are copied)
     const int any = __syncthreads_or(changed != 0);
     if (tid == 0) *stable = any ? 0 : 1;
+  } else if (tid == 0) {
+    *stable = 0;  // a block whose rows may move carries no flag into a later step in which they do not
   }
 }
 
