@@ -130,6 +130,121 @@ __global__ __launch_bounds__(1024) void k(unsigned long long* out, float* sink, 
   sink[blockIdx.x * blockDim.x + threadIdx.x] = a0 + a1 + a2 + a3 + a4 + a5 + a6 + a7 + acc0[0] + acc1[1] + acc2[2] + acc3[3] + q0[0] + q1[1] + q2[2] + q3[3];
 }
 
+// The attention kernel's tile loop without its memory traffic: two query blocks per wave, four softmax blocks per
+// "tile" with the MFMAs of the other block issued inside them in the kernel's order, operands from registers that stay
+// as they are.  PART: 0 = everything, 2 = no softmax arithmetic (conversions only).
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+__device__ __forceinline__ unsigned int pk_bf16(float a, float b) {
+  typedef __attribute__((ext_vector_type(2))) float f2;
+  typedef __attribute__((ext_vector_type(2))) __bf16 b2;
+  const f2 v = {a, b};
+  return __builtin_bit_cast(unsigned int, __builtin_convertvector(v, b2));
+}
+template <int PART>
+__global__ __launch_bounds__(512) void tile_loop(unsigned long long* out, float* sink, int iters) {
+  f32x16 o0[2], o1[2], sA, sB;
+  bf16x8 qf[2][4], kf[4], vf[2][2];
+  u32x4 pA[2], pB[2];
+  float mc[2] = {-3.f, -2.f}, l[2] = {0.f, 0.f};
+  const float c2 = 0.18f;
+  for (int i = 0; i < 16; ++i) { o0[0][i] = o0[1][i] = o1[0][i] = o1[1][i] = 0.f; sA[i] = 0.01f * (threadIdx.x + i); sB[i] = 0.02f * (threadIdx.x + i); }
+  for (int i = 0; i < 4; ++i) { qf[0][i] = qf[1][i] = kf[i] = bf16x8{1, 1, 1, 1, 1, 1, 1, 1}; vf[i >> 1][i & 1] = kf[i]; }
+  pA[0] = pA[1] = pB[0] = pB[1] = u32x4{0x3c003c00u, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u};
+  asm volatile("" : "+v"(sA), "+v"(sB));
+  auto qk = [&](f32x16& sv, int cb, int i) {
+    if constexpr (PART != 1) sv = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i], qf[cb][i], sv, 0, 0, 0);
+  };
+  auto pv = [&](int cb, const u32x4 (&pb)[2], int i) {
+    if constexpr (PART != 1) {
+      const bf16x8 p = __builtin_bit_cast(bf16x8, pb[i >> 1]);
+      if (i & 1) o1[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i >> 1][1], p, o1[cb], 0, 0, 0);
+      else o0[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i >> 1][0], p, o0[cb], 0, 0, 0);
+    }
+  };
+  auto softmax = [&](f32x16& sv, u32x4 (&pb)[2], float mcr, float& lsum, auto&& hook, int n_mfma) {
+    float psum = lsum;
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      hook(q4);
+#pragma unroll
+      for (int r = 4 * q4; r < 4 * q4 + 4; r += 2) {
+        unsigned int w;
+        if constexpr (PART == 2) {
+          w = pk_bf16(sv[r], sv[r + 1]);
+        } else {
+          const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r], c2, mcr));
+          const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r + 1], c2, mcr));
+          w = pk_bf16(p0, p1);
+          psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(__attribute__((ext_vector_type(2))) __bf16, w),
+                                                 __builtin_bit_cast(__attribute__((ext_vector_type(2))) __bf16, 0x3f803f80u), psum, false);
+        }
+        pb[r >> 3][(r >> 1) & 3] = w;
+      }
+    }
+    if (PART == 0) {
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        if (n_mfma == 2) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+          __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
+          __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+        } else {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+          __builtin_amdgcn_sched_group_barrier(0x400, 4, 0);
+          __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+        }
+      }
+    }
+    asm volatile("" : "+v"(pb[0]), "+v"(pb[1]));
+    lsum = psum;
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  __syncthreads();
+  const unsigned long long t0 = now();
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) qk(sA, 0, i);
+    softmax(sA, pA, mc[0], l[0], [&](int i) { qk(sB, 1, i); }, 1);
+    softmax(sB, pB, mc[1], l[1], [&](int i) { pv(0, pA, i); qk(sA, 0, i); }, 2);
+    softmax(sA, pA, mc[0], l[0], [&](int i) { pv(1, pB, i); qk(sB, 1, i); }, 2);
+    softmax(sB, pB, mc[1], l[1], [&](int i) { pv(0, pA, i); }, 1);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) pv(1, pB, i);
+    // keep the logits where they were (the products above would otherwise grow them without bound)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { sA[i] = 0.01f * i; sB[i] = 0.02f * i; }
+    asm volatile("" : "+v"(sA), "+v"(sB));
+  }
+  const unsigned long long t1 = now();
+  if ((threadIdx.x & 63) == 0) out[blockIdx.x * 16 + (threadIdx.x >> 6)] = t1 - t0;
+  float acc = l[0] + l[1];
+  for (int i = 0; i < 16; ++i) acc += o0[0][i] + o0[1][i] + o1[0][i] + o1[1][i] + sA[i] + sB[i];
+  sink[blockIdx.x * blockDim.x + threadIdx.x] = acc;
+}
+
+template <int PART>
+void run_tile(const char* name, int threads, unsigned long long* dout, float* sink) {
+  const int iters = 500, blocks = 256;
+  hipLaunchKernelGGL(tile_loop<PART>, dim3(blocks), dim3(threads), 0, 0, dout, sink, 10);
+  (void)hipDeviceSynchronize();
+  hipEvent_t e0, e1;
+  (void)hipEventCreate(&e0); (void)hipEventCreate(&e1);
+  (void)hipEventRecord(e0);
+  hipLaunchKernelGGL(tile_loop<PART>, dim3(blocks), dim3(threads), 0, 0, dout, sink, iters);
+  (void)hipEventRecord(e1);
+  (void)hipDeviceSynchronize();
+  float ms = 0.f;
+  (void)hipEventElapsedTime(&ms, e0, e1);
+  std::vector<unsigned long long> h(blocks * 16);
+  if (hipMemcpy(h.data(), dout, h.size() * 8, hipMemcpyDeviceToHost) != hipSuccess) { printf("copy failed\n"); return; }
+  printf("%-44s waves/SIMD %d: wave 0 %7.1f cycles per tile; launch %7.1f ns per tile\n", name, threads / 256, (double)h[0] / iters,
+         ms * 1e6 / iters);
+}
+
 template <int MODE>
 void run(const char* name, int per_iter, int threads, unsigned long long* dout, float* sink) {
   const int iters = 2000, blocks = 256;
@@ -169,6 +284,10 @@ int main() {
     run<10>("16 mfma + 96 fma + 32 exp", 144, threads, dout, sink);
     run<11>("32 mfma 16x16x32", 32, threads, dout, sink);
     run<12>("32 mfma 16x16x32 + 128 fma", 160, threads, dout, sink);
+  }
+  for (int threads : {256, 512}) {
+    run_tile<0>("tile loop of the attention kernel, registers only", threads, dout, sink);
+    run_tile<2>("  without its softmax arithmetic", threads, dout, sink);
   }
   return 0;
 }
