@@ -174,6 +174,25 @@ def test_unpruned_cache_is_rewritten_in_place_and_settles(bits, G):
     ctx.destroy()
 
 
+def test_blocks_settled_while_the_cache_grew_are_not_skipped_once_their_rows_move():
+    """While a budgeted cache is still growing no row moves, and old blocks settle as they do without a budget;
+    from the first pruning step on only the first frame's blocks keep their place.  The blocks beyond it lose their
+    flag (they are re-quantized every step from then on), and every byte still equals the oracle's."""
+    spec = CONFIGS[0].with_(name="grow-then-prune", n_heads=2, tokens_per_frame=96, n_special=5, budget=640, kv_bits=4,
+                            group_size=64, n_layers=1, seed=43)
+    ctx, st = parity.make_pair(spec)
+    src = FrameSource(spec, DEV)
+    settled = []
+    for f in range(12):  # 6 frames fit the budget (576 tokens), the 7th triggers the first pruning
+        q, k, v = src.frame(f)
+        parity.step_and_compare(ctx, st, spec, 0, 0, q[0], k[0], v[0])
+        settled.append(ctx.settled_blocks(0)[0])
+    print("  settled (head, block) pairs per frame:", settled, flush=True)
+    assert max(settled[:7]) > 2 * 1                    # during growth more than the first frame's one whole block per head
+    assert all(x <= 2 * 1 for x in settled[8:])        # afterwards at most that block (96 tokens = 1 whole block of 64)
+    ctx.destroy()
+
+
 @pytest.mark.parametrize("rising", [True, False])
 @pytest.mark.parametrize("bits,splits", [(16, 1), (4, 1), (4, 3)])
 def test_logits_that_drift_far_along_the_key_axis(rising, bits, splits):
