@@ -61,9 +61,11 @@ typedef struct {
 typedef struct {
   const void* ptr;      /* DEVICE, bf16, 16-byte aligned */
   int64_t stride_head;  /* elements, >= 0, a multiple of 8 */
-  int64_t stride_token; /* elements, a multiple of 8, >= head_dim and <= 2^24 (rows are fetched
-                           in 16-byte pieces through 32-bit buffer offsets); anything else is
-                           XSV_ERR_ARG */
+  int64_t stride_token; /* elements, a multiple of 8, >= head_dim and <= 2^24; for K and V the rows
+                           of one head of a frame must lie within 2 GiB,
+                           ((tokens_per_frame - 1) * stride_token + head_dim) * 2 <= 2^31 (they are
+                           fetched in 16-byte pieces through 32-bit byte offsets); anything else
+                           is XSV_ERR_ARG */
 } xsv_tensor;
 
 /* ---- life cycle ------------------------------------------------------------------------------- */

@@ -213,6 +213,11 @@ int fill_batch(xsv_ctx* ctx, Batch& b, int layer0, int n_layers, const xsv_tenso
   std::memset(&b, 0, sizeof(b));
   b.n_layers = n_layers;
   b.layer0 = layer0;
+  // the frame's K and V rows of one head are read through a buffer resource with 32-bit byte offsets: the rows of a
+  // head must lie within 2 GiB of its first one
+  const long long n_rows = ctx->cfg.tokens_per_frame;
+  auto span_ok = [&](const xsv_tensor& t) { return ((n_rows - 1) * t.stride_token + kD) * 2 <= (1ll << 31); };
+  if ((k && n_layers > 0 && !span_ok(k[0])) || (v && n_layers > 0 && !span_ok(v[0]))) return XSV_ERR_ARG;
   for (int i = 0; i < n_layers; ++i) {
     if (ctx->layers[layer0 + i].buf) b.bufsel |= 1u << i;
     if (q) {

@@ -418,6 +418,18 @@ def test_bad_arguments_are_rejected_before_anything_is_launched():
     torch.cuda.synchronize()
     assert ctx.cache_len(0) == n
     ctx.destroy()
+    # K / V rows of one head that would spread over more than 2 GiB (32-bit byte offsets inside the kernel)
+    spec2 = CONFIGS[0].with_(tokens_per_frame=150, budget=0)
+    ctx2 = xsv.Context.from_spec(spec2, max_frames=2)
+    q2, k2, v2 = (t[0] for t in FrameSource(spec2, DEV).frame(0))
+    out2 = torch.empty_like(q2)
+    wide = xsv.xsv_tensor(k2.data_ptr(), k2.stride(0), 1 << 24)
+    assert lib.xsv_step(ctx2._h, 0, T(q2), wide, T(v2), out2.data_ptr()) == xsv.XSV_ERR_ARG
+    assert lib.xsv_step(ctx2._h, 0, T(q2), T(k2), wide, out2.data_ptr()) == xsv.XSV_ERR_ARG
+    assert lib.xsv_frame_attend(ctx2._h, T(q2), wide, T(v2), out2.data_ptr()) == xsv.XSV_ERR_ARG
+    ctx2.step(0, q2, k2, v2, out2)
+    assert ctx2.cache_len(0) == 150
+    ctx2.destroy()
 
 
 def test_batched_call_with_mismatched_strides_launches_nothing():
