@@ -343,6 +343,19 @@ __global__ __launch_bounds__(256) void requant_kernel(const RequantArgs a) {
   }
 }
 
+// Clears the block flags (a kernel rather than a memset node: a caller may capture the stream, and memset nodes in
+// captured graphs have replayed wrongly on this platform).
+__global__ __launch_bounds__(256) void zero_bytes_kernel(uint8_t* p, size_t n) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+
+hipError_t launch_zero_bytes(uint8_t* p, size_t n, hipStream_t stream) {
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(zero_bytes_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, p, n);
+  return hipGetLastError();
+}
+
 hipError_t launch_requant(const RequantArgs& a, hipStream_t stream) {
   if (a.Tn <= 0) return hipSuccess;
   const dim3 grid((a.Tn + kTile - 1) / kTile, a.pool.H, a.b.n_layers);

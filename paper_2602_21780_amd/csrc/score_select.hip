@@ -170,13 +170,31 @@ __global__ __launch_bounds__(256) void score_kernel(const ScoreArgs a) {
       if (h < hn) {
         float x[16];  // head h's key row (this thread's 16 channels), dequantized view
         if constexpr (kQuant) {
-          constexpr uint32_t mask = (1u << (BITS & 15)) - 1u;
           const float* ks = prm + ((h * kGroups + (r / G) % kGroups) * 2) * kD + cq * 16;
           const float* kz = ks + kD;
+          // codes to floats by bytes: one mask per 4 (4-bit: per 8) codes, then one byte-to-float conversion each,
+          // instead of a bit-field extract and a conversion per code
+          float code[16];
 #pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            const uint32_t code = (w[h][(e * BITS) / 32] >> ((e * BITS) % 32)) & mask;
-            x[e] = round_bf16(((float)code - kz[e]) * ks[e]);
+          for (int d = 0; d < kDwT; ++d) {
+            constexpr int kPerDw = 32 / BITS;  // 8 or 16 codes per dword
+#pragma unroll
+            for (int sft = 0; sft < 8 / BITS; ++sft) {  // code e of the dword sits in byte e / (8 / BITS) of (w >> BITS * (e % (8 / BITS))) & mask
+              uint32_t t = (w[h][d] >> (BITS * sft)) & (BITS == 4 ? 0x0f0f0f0fu : 0x03030303u);
+              asm volatile("" : "+v"(t));  // (keeps the mask shared by the four conversions below)
+#pragma unroll
+              for (int b = 0; b < 4; ++b) code[d * kPerDw + b * (8 / BITS) + sft] = (float)((t >> (8 * b)) & 0xffu);
+            }
+          }
+          // canonical view, rounded to bf16 in pairs (one packed conversion per two values)
+#pragma unroll
+          for (int e = 0; e < 16; e += 2) {
+            typedef __attribute__((ext_vector_type(2))) float f2;
+            typedef __attribute__((ext_vector_type(2))) __bf16 b2;
+            const f2 v = {(code[e] - kz[e]) * ks[e], (code[e + 1] - kz[e + 1]) * ks[e + 1]};
+            const uint32_t pk = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, b2));
+            x[e] = bf16_lo(pk);
+            x[e + 1] = bf16_hi(pk);
           }
         } else {
 #pragma unroll

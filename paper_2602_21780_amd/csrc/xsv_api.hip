@@ -575,7 +575,7 @@ int xsv_reset(xsv_ctx* ctx) {
   if (rc != XSV_OK) return rc;
   for (LayerState& L : ctx->layers) L = LayerState();
   const size_t flags = (size_t)ctx->cfg.n_layers * ctx->cfg.n_heads * (ctx->pool.Tcap / kTile);
-  if (hipMemsetAsync(ctx->stable_flag, 0, flags, ctx->stream) != hipSuccess) return hip_fail(ctx);
+  if (launch_zero_bytes(ctx->stable_flag, flags, ctx->stream) != hipSuccess) return hip_fail(ctx);
   return XSV_OK;
 }
 

@@ -197,6 +197,7 @@ struct RequantArgs {
   uint8_t* stable_flag;  // [L][H][Tcap / 64]
 };
 hipError_t launch_requant(const RequantArgs& a, hipStream_t stream);
+hipError_t launch_zero_bytes(uint8_t* p, size_t n, hipStream_t stream);  // a fill kernel (no memset node)
 
 // Canonical (one code per byte, untransposed) copies of one layer buffer → device arrays.
 struct UnpackArgs {
