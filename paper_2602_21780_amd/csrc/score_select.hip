@@ -12,10 +12,9 @@
 //   Per-head variant (ScoreArgs::per_head, not the paper's): the averages over heads are left out,
 //   qtilde_h comes from head h's partial alone and head h's keys give head h's own score vector.
 //   select_kernel       exact top-k by radix select on order-preserving integer keys held in
-//                       registers (4 passes of 8 bits, histograms in LDS, one barrier per pass: every
-//                       wave finds the bin by itself with a prefix sum on the ALU's lane-shift paths),
-//                       ties at the threshold resolved toward smaller positions, then an ordered
-//                       compaction that emits the keep list ascending.
+//                       registers (4 passes of 8 bits, histograms in LDS, bin search by a shuffle
+//                       scan), ties at the threshold resolved toward smaller positions, then an
+//                       ordered compaction that emits the keep list ascending.
 // Compiled with -ffp-contract=off: the dequantized view must be (code - zero) * scale with one
 // rounding per operation.
 #include "xsv_internal.h"
@@ -258,44 +257,40 @@ __device__ __forceinline__ uint32_t order_key(float f) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-constexpr int kSelThreads = 256;  // 4 waves: cheap barriers
+constexpr int kSelThreads = 256;  // 4 waves: cheap barriers; one histogram bin per thread
 
-// inclusive prefix sum over the 64 lanes of a wave in the lanes' order, on the data-parallel-primitive paths of the
-// vector ALU (shifts inside rows of 16 lanes, then the last lane of a row broadcast to the rows behind it): six
-// additions, no trip through the LDS crossbar as a lane shuffle takes
-__device__ __forceinline__ int wave_inclusive_sum(int v) {
-  v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);  // row_shr:1, lanes without a source read 0
-  v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);  // row_shr:2
-  v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);  // row_shr:4
-  v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);  // row_shr:8
-  v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1 and 3
-  v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);  // row_bcast:31 into rows 2 and 3
-  return v;
-}
-
-// exclusive prefix sums of two counters over the workgroup's threads, in thread order (one barrier)
-__device__ __forceinline__ void block_exclusive_scan2(int& a, int& b, int* sh /* 2*16 */) {
+// exclusive prefix sums of two counters over the workgroup's threads, in thread order
+__device__ __forceinline__ void block_exclusive_scan2(int& a, int& b, int* sh /* 2*16 */, int& total_a, int& total_b) {
   static_assert(kSelThreads / 64 <= 16, "wave totals live in 16 slots");
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int ia = wave_inclusive_sum(a), ib = wave_inclusive_sum(b);
+  int ia = a, ib = b;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const int ta = __shfl_up(ia, d), tb = __shfl_up(ib, d);
+    if (lane >= d) { ia += ta; ib += tb; }
+  }
   if (lane == 63) { sh[wave] = ia; sh[16 + wave] = ib; }
   __syncthreads();
   int oa = 0, ob = 0;
+  total_a = 0; total_b = 0;
   for (int w = 0; w < kSelThreads / 64; ++w) {
     if (w < wave) { oa += sh[w]; ob += sh[16 + w]; }
+    total_a += sh[w]; total_b += sh[16 + w];
   }
   a = oa + ia - a;
   b = ob + ib - b;
+  __syncthreads();
 }
 
 // one workgroup per list (layer, or layer and head); KPT > 0: each thread keeps its (at most KPT) keys in registers
 template <int KPT>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectArgs a) {
-  constexpr int kStage = KPT > 0 ? KPT * kSelThreads + KPT * kSelThreads / 32 + 32 : 1;  // keys + padding
-  __shared__ uint32_t stage[kStage];
-  __shared__ int hist[4][256];  // one histogram per radix pass, all cleared up front
+  __shared__ int hist[256];
+  __shared__ int wave_tot[4];
   __shared__ int sh_scan[32];
-  const int tid = threadIdx.x, lane = tid & 63;
+  __shared__ uint32_t sh_prefix;
+  __shared__ int sh_need;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const float* scores = a.scores + (size_t)blockIdx.x * a.scores_stride;
   int32_t* keep = a.keep + (size_t)blockIdx.x * a.keep_stride;
   const int P = a.P, k = a.k;
@@ -303,64 +298,56 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectArgs a)
   // thread t owns the contiguous positions [t*per, (t+1)*per)
   const int per = (P + kSelThreads - 1) / kSelThreads;
   const int j0 = min(P, tid * per), j1 = min(P, j0 + per);
-#pragma unroll
-  for (int i = 0; i < 4; ++i) hist[i][tid] = 0;
   uint32_t keys[KPT > 0 ? KPT : 1];
   if constexpr (KPT > 0) {
-    // The scores are read in the order they lie in memory (a wave's load covers 256 consecutive bytes) and handed to
-    // their owners through LDS; position j sits at j + j / 32, so that the owners' reads - `per` apart - spread over
-    // the banks whatever `per` is.
-    float raw[KPT];  // all loads in flight before the first is waited for
 #pragma unroll
-    for (int i = 0; i < KPT; ++i) raw[i] = (tid + i * kSelThreads < P) ? scores[tid + i * kSelThreads] : 0.f;
-#pragma unroll
-    for (int i = 0; i < KPT; ++i) {
-      const int j = tid + i * kSelThreads;
-      if (j < P) stage[j + (j >> 5)] = order_key(raw[i]);
-    }
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < KPT; ++i) keys[i] = (j0 + i < j1) ? stage[(j0 + i) + ((j0 + i) >> 5)] : 0u;
-  } else {
-    __syncthreads();
+    for (int i = 0; i < KPT; ++i) keys[i] = (j0 + i < j1) ? order_key(scores[j0 + i]) : 0u;
   }
   auto key_at = [&](int i) -> uint32_t {  // i-th key of this thread
     if constexpr (KPT > 0) return keys[i];
     else return order_key(scores[j0 + i]);
   };
 
-  // k-th largest key by radix select, most significant byte first.  Per pass: histogram of the byte among the keys
-  // that share the prefix found so far, one barrier, then EVERY wave walks the 256 bins from the top (four bins per
-  // lane, a prefix sum over the lanes) and finds the bin that holds the wanted rank by itself - nothing to publish,
-  // no second barrier.
+  // k-th largest key by radix select, most significant byte first
   uint32_t prefix = 0;
   int need = k;  // rank still to find inside the current prefix class (1-based from the top)
 #pragma unroll
   for (int pass = 0; pass < 4; ++pass) {
     const int shift = 24 - 8 * pass;
+    hist[tid] = 0;
+    __syncthreads();
     const uint32_t hi_mask = pass == 0 ? 0u : (0xffffffffu << (shift + 8));
     if constexpr (KPT > 0) {
 #pragma unroll
       for (int i = 0; i < KPT; ++i)
-        if (j0 + i < j1 && (keys[i] & hi_mask) == prefix) atomicAdd(&hist[pass][(keys[i] >> shift) & 255u], 1);
+        if (j0 + i < j1 && (keys[i] & hi_mask) == prefix) atomicAdd(&hist[(keys[i] >> shift) & 255u], 1);
     } else {
       for (int i = 0; i < j1 - j0; ++i) {
         const uint32_t key = key_at(i);
-        if ((key & hi_mask) == prefix) atomicAdd(&hist[pass][(key >> shift) & 255u], 1);
+        if ((key & hi_mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
       }
     }
     __syncthreads();
-    // lane l looks at bins 255 - 4l .. 252 - 4l; `above` = keys in higher bins
-    const int top_bin = 255 - 4 * lane;
-    const int c0 = hist[pass][top_bin], c1 = hist[pass][top_bin - 1], c2 = hist[pass][top_bin - 2], c3 = hist[pass][top_bin - 3];
-    const int mine = c0 + c1 + c2 + c3;
-    const int above = wave_inclusive_sum(mine) - mine;
-    const bool here = above < need && need <= above + mine;  // exactly one lane (need <= number of keys in the class)
-    int bin = top_bin, rest = need - above;  // the bin inside this lane's four, and the rank inside that bin
-    if (rest > c0) { rest -= c0; --bin; if (rest > c1) { rest -= c1; --bin; if (rest > c2) { rest -= c2; --bin; } } }
-    const int src = __builtin_ctzll(__ballot(here));
-    prefix |= (uint32_t)__builtin_amdgcn_readlane(bin, src) << shift;
-    need = __builtin_amdgcn_readlane(rest, src);
+    // bin b holds the wanted rank iff  (#keys in bins above b) < need <= (that + hist[b]);
+    // suffix sums over the 256 bins: per-wave shuffle scan + 4 wave totals
+    const int h = hist[tid];
+    int incl = h;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const int v = __shfl_down(incl, d);
+      if (lane + d < 64) incl += v;
+    }
+    if (lane == 0) wave_tot[wave] = incl;
+    __syncthreads();
+    int above = incl - h;
+    for (int w = wave + 1; w < 4; ++w) above += wave_tot[w];
+    if (above < need && need <= above + h) {
+      sh_prefix = prefix | ((uint32_t)tid << shift);
+      sh_need = need - above;
+    }
+    __syncthreads();
+    prefix = sh_prefix;
+    need = sh_need;
   }
   const uint32_t thr = prefix;  // key of the k-th largest score
   const int need_eq = need;     // how many of the scores equal to it are kept (smallest positions)
@@ -372,8 +359,8 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectArgs a)
     n_gt += key > thr;
     n_eq += key == thr;
   }
-  int gt_before = n_gt, eq_before = n_eq;
-  block_exclusive_scan2(gt_before, eq_before, sh_scan);
+  int gt_before = n_gt, eq_before = n_eq, tot_gt, tot_eq;
+  block_exclusive_scan2(gt_before, eq_before, sh_scan, tot_gt, tot_eq);
   int out = a.T_first + gt_before + min(eq_before, need_eq);
   int eq_rank = eq_before;
   for (int i = 0; i < j1 - j0; ++i) {
@@ -390,7 +377,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectArgs a)
 }
 
 hipError_t launch_select(const SelectArgs& a, hipStream_t stream) {
-  static_assert(kSelThreads == 256, "the histograms are cleared one bin per thread");
+  static_assert(kSelThreads == 256, "one histogram bin per thread");
   if (a.P <= 16 * kSelThreads) hipLaunchKernelGGL(select_kernel<16>, dim3(a.n_lists), dim3(kSelThreads), 0, stream, a);
   else if (a.P <= 32 * kSelThreads) hipLaunchKernelGGL(select_kernel<32>, dim3(a.n_lists), dim3(kSelThreads), 0, stream, a);
   else hipLaunchKernelGGL(select_kernel<0>, dim3(a.n_lists), dim3(kSelThreads), 0, stream, a);
