@@ -755,6 +755,9 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const AttendArgs a) {
 // a unit's edge has nothing to merge.
 // Thread = (row, lane half hh, quarter of the lane's 32 values): 8 fp16 values of every piece.
 __global__ __launch_bounds__(256) void combine_kernel(const AttendArgs a) {
+  // the merge shares its compute units with the chain's kernels of the same layer, which nothing waits for: its
+  // waves are served first
+  __builtin_amdgcn_s_setprio(3);
   const int H = a.H, n = a.n;
   const int nqb = (n + a.rows_wg - 1) / a.rows_wg;
   const int n_tiles = (a.Tc + kTile - 1) / kTile + (n + kTile - 1) / kTile;
