@@ -33,7 +33,7 @@ class _Config(C.Structure):
         ("n_layers", C.c_int32), ("n_heads", C.c_int32), ("head_dim", C.c_int32),
         ("tokens_per_frame", C.c_int32), ("n_special", C.c_int32), ("budget", C.c_int32),
         ("kv_bits", C.c_int32), ("group_size", C.c_int32), ("pool_size", C.c_int32),
-        ("softmax_scale", C.c_float), ("score_mode", C.c_int32),
+        ("softmax_scale", C.c_float), ("score_mode", C.c_int32), ("value_mode", C.c_int32),
     ]
 
 
@@ -177,9 +177,9 @@ class RefStream:
     """One oracle stream: `n_layers` independent caches stepped frame by frame."""
 
     def __init__(self, n_layers, n_heads, head_dim, tokens_per_frame, n_special, budget, kv_bits,
-                 group_size, pool_size=16, softmax_scale=0.0, score_mode=0):
+                 group_size, pool_size=16, softmax_scale=0.0, score_mode=0, value_mode=0):
         self.cfg = _Config(n_layers, n_heads, head_dim, tokens_per_frame, n_special, budget, kv_bits,
-                           group_size, pool_size, softmax_scale, score_mode)
+                           group_size, pool_size, softmax_scale, score_mode, value_mode)
         self._h = lib().xsv_ref_create(C.byref(self.cfg))
         if not self._h:
             raise ValueError("xsv_ref_create rejected the configuration")

@@ -335,6 +335,13 @@ struct xsv_ref_config {
   //    with its own pooled queries and keeps its own top-k.  All heads still keep the same NUMBER of
   //    tokens, so the cache length stays one number per layer.
   int32_t score_mode;
+  // 0: the whole retained cache is quantized anew every step (the reading of Sec. 3.3 used throughout: quantization is
+  //    applied to the final cache, history through its dequantized view).
+  // 1: a variant, "quantize once" for the values: a value row is quantized when its frame is appended, and a row that
+  //    is retained keeps those codes, its scale and its zero point for as long as it stays in the cache (a value row's
+  //    groups are its own channels, so nothing about them depends on which other tokens are retained).  Keys are
+  //    quantized anew as in mode 0: their groups are runs of consecutive RETAINED tokens and change with every pruning.
+  int32_t value_mode;
 };
 
 // "sets" below = index sets per layer: 1 (score_mode 0) or H (score_mode 1, set s belongs to head s).
@@ -359,6 +366,7 @@ xsv_ref_state* xsv_ref_create(const xsv_ref_config* cfg) {
   if (cfg->kv_bits != 2 && cfg->kv_bits != 4 && cfg->kv_bits != 16) return nullptr;
   if (cfg->kv_bits != 16 && (cfg->group_size <= 0 || cfg->head_dim % cfg->group_size != 0)) return nullptr;
   if (cfg->score_mode != 0 && cfg->score_mode != 1) return nullptr;
+  if (cfg->value_mode != 0 && cfg->value_mode != 1) return nullptr;
   auto* st = new xsv_ref_state;
   st->cfg = *cfg;
   if (st->cfg.softmax_scale == 0.0f) st->cfg.softmax_scale = 1.0f / std::sqrt(static_cast<float>(cfg->head_dim));
@@ -516,6 +524,14 @@ int xsv_ref_step(xsv_ref_state* st, int layer, const uint16_t* q, const uint16_t
   } else {
     const int G = c.group_size;
     const size_t n_el = static_cast<size_t>(H) * Tn * d;
+    // (value_mode 1: what the retained rows held before this step, to be put back below)
+    std::vector<uint8_t> v_codes_old;
+    std::vector<float> v_scale_old, v_zero_old;
+    if (c.value_mode == 1) {
+      v_codes_old = L.v_codes;
+      v_scale_old = L.v_scale;
+      v_zero_old = L.v_zero;
+    }
     L.k_codes.assign(n_el, 0);
     L.v_codes.assign(n_el, 0);
     L.k_scale.assign(static_cast<size_t>(H) * ceil_div(Tn, G) * d, 0.0f);
@@ -524,6 +540,23 @@ int xsv_ref_step(xsv_ref_state* st, int layer, const uint16_t* q, const uint16_t
     L.v_zero.assign(L.v_scale.size(), 0.0f);
     xsv_ref_quantize_k(k_kept.data(), H, Tn, d, c.kv_bits, G, L.k_codes.data(), L.k_scale.data(), L.k_zero.data());
     xsv_ref_quantize_v(v_kept.data(), H, Tn, d, c.kv_bits, G, L.v_codes.data(), L.v_scale.data(), L.v_zero.data());
+    if (c.value_mode == 1) {
+      // quantize once: a row that came from the cache keeps the codes and parameters it had there
+      const int vg = d / G;
+      for (int h = 0; h < H; ++h) {
+        const std::vector<int32_t>& kp = keep[sets == 1 ? 0 : h];
+        for (int i = 0; i < Tn; ++i) {
+          const int src = kp[i];
+          if (src >= Tc) continue;  // a row of the current frame: quantized just now, for good
+          for (int ch = 0; ch < d; ++ch)
+            L.v_codes[(static_cast<size_t>(h) * Tn + i) * d + ch] = v_codes_old[(static_cast<size_t>(h) * Tc + src) * d + ch];
+          for (int g = 0; g < vg; ++g) {
+            L.v_scale[(static_cast<size_t>(h) * Tn + i) * vg + g] = v_scale_old[(static_cast<size_t>(h) * Tc + src) * vg + g];
+            L.v_zero[(static_cast<size_t>(h) * Tn + i) * vg + g] = v_zero_old[(static_cast<size_t>(h) * Tc + src) * vg + g];
+          }
+        }
+      }
+    }
   }
   L.T = Tn;
   L.frames += 1;
