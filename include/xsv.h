@@ -56,6 +56,12 @@ typedef struct {
                                its own pooled queries and keeps its own top-k (same count for all heads) */
   float softmax_scale;      /* 0 → 1/sqrt(head_dim)                                            */
   int32_t max_frames;       /* only for budget == 0: frames the cache must be able to hold     */
+  int32_t value_mode;       /* 0: the whole retained cache is quantized anew every step (Sec. 3.3 applied to the
+                               final cache, history through its dequantized view).
+                               1: a variant, "quantize once" for the values: a value row is quantized when its
+                               frame is appended and keeps those codes, its scale and its zero point while it is
+                               retained (its groups are its own channels).  Keys are quantized anew either way:
+                               their groups are runs of retained tokens.  No effect with kv_bits == 16. */
 } xsv_config;
 
 typedef struct {

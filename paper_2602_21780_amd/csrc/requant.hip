@@ -257,9 +257,13 @@ __global__ __launch_bounds__(256) void requant_kernel(const RequantArgs a) {
   }
 
   // ---------------- values ----------------
+  // "quantize once" (carry_values): a row that comes from the cache keeps its codes and parameters; a wave whose rows
+  // all do skips the arithmetic altogether
+  const bool carry = kQuant && a.carry_values && from_cache;
+  const bool all_carried = kQuant && a.carry_values && __all(from_cache || !row_valid);
 #pragma unroll
   for (int e = 0; e < 16; ++e) x[e] = 0.f;
-  if (from_cache) {
+  if (from_cache && !all_carried) {
     if constexpr (kQuant) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
@@ -276,31 +280,41 @@ __global__ __launch_bounds__(256) void requant_kernel(const RequantArgs a) {
   }
 
   if constexpr (kQuant) {
-    float lo = x[0], hi = x[0];
+    uint32_t vcode[16];
+    QParam q;
+    q.s = v_ps; q.z = v_pz; q.y = 0.f; q.safe = true;
+    if (!all_carried) {  // (wave-uniform: the lane exchanges below are taken by whole waves)
+      float lo = x[0], hi = x[0];
 #pragma unroll
-    for (int e = 1; e < 16; ++e) { lo = fminf(lo, x[e]); hi = fmaxf(hi, x[e]); }
-    // the G channels of a group sit in G/16 neighbouring threads of the same token
-    lo = fminf(lo, __shfl_xor(lo, 1));
-    hi = fmaxf(hi, __shfl_xor(hi, 1));
-    if (G == 64) {
-      lo = fminf(lo, __shfl_xor(lo, 2));
-      hi = fmaxf(hi, __shfl_xor(hi, 2));
+      for (int e = 1; e < 16; ++e) { lo = fminf(lo, x[e]); hi = fmaxf(hi, x[e]); }
+      // the G channels of a group sit in G/16 neighbouring threads of the same token
+      lo = fminf(lo, __shfl_xor(lo, 1));
+      hi = fmaxf(hi, __shfl_xor(hi, 1));
+      if (G == 64) {
+        lo = fminf(lo, __shfl_xor(lo, 2));
+        hi = fmaxf(hi, __shfl_xor(hi, 2));
+      }
+      q = group_param(lo, hi, BITS);
+      if (__all(q.safe)) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) vcode[e] = quant_code_fast(x[e], q.s, q.y, q.z, BITS);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) vcode[e] = quant_code(x[e], q.s, q.z, BITS);
+      }
     }
-    const QParam q = group_param(lo, hi, BITS);
+    if (carry) {  // the row's own codes and parameters, as read
+      q.s = v_ps;
+      q.z = v_pz;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) vcode[e] = (vraw[e] >> v_shift) & kMask;
+    }
     if (row_valid && (cq * 16) % G == 0) {
       const size_t gidx = ((size_t)h * Tcap + (size_t)u * kTile + r) * kVGroups + (cq * 16) / G;
       dst.vs[gidx] = q.s;
       dst.vz[gidx] = q.z;
     }
     if (candidate && row_valid) changed |= (__float_as_uint(v_ps) ^ __float_as_uint(q.s)) | (__float_as_uint(v_pz) ^ __float_as_uint(q.z));
-    uint32_t vcode[16];
-    if (__all(q.safe)) {
-#pragma unroll
-      for (int e = 0; e < 16; ++e) vcode[e] = quant_code_fast(x[e], q.s, q.y, q.z, BITS);
-    } else {
-#pragma unroll
-      for (int e = 0; e < 16; ++e) vcode[e] = quant_code(x[e], q.s, q.z, BITS);
-    }
 #pragma unroll
     for (int e = 0; e < 16; ++e) vt[cq * 16 + e][r] = row_valid ? (uint16_t)vcode[e] : (uint16_t)0;
     if (candidate && row_valid) {

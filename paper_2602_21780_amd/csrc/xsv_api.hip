@@ -402,6 +402,7 @@ int do_quantize(xsv_ctx* ctx, int layer0, int n_layers, const xsv_tensor* k, con
     r.identity_end = p.prune ? std::min(p.T_first, r.Tc) : r.Tc;
     r.stable_blocks = r.identity_end / kTile;
     r.stable_flag = ctx->stable_flag;
+    r.carry_values = ctx->cfg.value_mode == 1;
   }
   if (launch_requant(r, ctx->work) != hipSuccess) return hip_fail(ctx);
   for (int i = 0; i < n_layers; ++i) {
@@ -466,6 +467,7 @@ int xsv_create(const xsv_config* cfg, void* hip_stream, xsv_ctx** out) {
     return XSV_ERR_ARG;
   if (c.kv_bits != 2 && c.kv_bits != 4 && c.kv_bits != 16) return XSV_ERR_ARG;
   if (c.score_mode != 0 && c.score_mode != 1) return XSV_ERR_ARG;
+  if (c.value_mode != 0 && c.value_mode != 1) return XSV_ERR_ARG;
   if (c.head_dim != kD) return XSV_ERR_UNSUPPORTED;
   if (c.kv_bits == 16) c.group_size = 64;
   if (c.group_size != 32 && c.group_size != 64) return c.group_size > 0 ? XSV_ERR_UNSUPPORTED : XSV_ERR_ARG;

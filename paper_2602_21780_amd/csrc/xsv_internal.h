@@ -195,6 +195,7 @@ struct RequantArgs {
   // bit - flagged per (layer, head, block) by the step that saw it happen - it never changes again and is skipped
   int stable_blocks;
   uint8_t* stable_flag;  // [L][H][Tcap / 64]
+  int carry_values;      // xsv_config.value_mode == 1: value rows that come from the cache keep their codes and parameters
 };
 hipError_t launch_requant(const RequantArgs& a, hipStream_t stream);
 hipError_t launch_zero_bytes(uint8_t* p, size_t n, hipStream_t stream);  // a fill kernel (no memset node)

@@ -45,11 +45,11 @@ def cache_bytes(spec, T):
     return 2 * T * D * per * spec.n_layers
 
 
-def run_stream(spec, frames, checkpoints, torch, xsv, FrameSource, window=5, score_mode=0):
+def run_stream(spec, frames, checkpoints, torch, xsv, FrameSource, window=5, score_mode=0, value_mode=0):
     """Steps `frames` frames; returns rows (frame, ms/frame averaged over the `window` frames ending there)."""
     dev = "cuda:0"
     L, n = spec.n_layers, spec.tokens_per_frame
-    ctx = xsv.Context.from_spec(spec, max_frames=frames + 1, score_mode=score_mode)
+    ctx = xsv.Context.from_spec(spec, max_frames=frames + 1, score_mode=score_mode, value_mode=value_mode)
     ctx.set_overlap(2)
     src = FrameSource(spec, dev)
     out = torch.empty((L, spec.n_heads, n, spec.head_dim), dtype=torch.bfloat16, device=dev)
@@ -228,6 +228,56 @@ def frame_attention(torch, xsv, FrameSource, CONFIGS, reps=20):
     return rows
 
 
+def value_mode_study(torch, xsv, FrameSource, CONFIGS):
+    """Values quantized once (value_mode 1) against everything re-quantized every step (0), 24-layer workload at its
+    saturated cache: the re-quantize launch with all layers per launch on one stream (events of the library), and
+    frames/s layer by layer in both overlap modes (best of three runs of 20 frames)."""
+    import time
+    spec = CONFIGS[2]
+    L, n = spec.n_layers, spec.tokens_per_frame
+    src = FrameSource(spec, "cuda:0")
+    frames = [src.frame(f) for f in range(28)]
+    out = torch.empty((L, spec.n_heads, n, spec.head_dim), dtype=torch.bfloat16, device="cuda:0")
+    requant_bytes = 2 * (4096 - n) * 1024 * 0.625 + 4 * n * 1024 + 2 * 4096 * 1024 * 0.625   # per layer, as in bench.py
+    rows = []
+    for vm in (0, 1):
+        ctx = xsv.Context.from_spec(spec, value_mode=vm)
+        ctx.set_overlap(0)
+        packed = [ctx.pack_layers(q, k, v, out) for (q, k, v) in frames]
+        for f in range(8):
+            ctx.step_all_layers(packed=packed[f])
+        ctx.set_attend_timing(True)
+        for f in range(8, 14):
+            ctx.step_all_layers(packed=packed[f])
+        torch.cuda.synchronize()
+        _, sp, rq = ctx.chain_times()
+        ctx.destroy()
+        row = {"value_mode": vm, "requant_24_layers_us": round(1e3 * rq, 1),
+               "requant_GBs": round(L * requant_bytes / (rq * 1e-3) / 1e9, 0)}
+        for mode in (2, 1):
+            ctx = xsv.Context.from_spec(spec, value_mode=vm)
+            ctx.set_overlap(mode)
+            pk = [[ctx.pack_step(q[l], k[l], v[l], out[l]) for l in range(L)] for (q, k, v) in frames]
+            for f in range(8):
+                for l in range(L):
+                    ctx.step_packed(l, pk[f][l])
+                ctx.join()
+            torch.cuda.synchronize()
+            best = 0.0
+            for _ in range(3):
+                t0 = time.perf_counter()
+                for f in range(8, 28):
+                    for l in range(L):
+                        ctx.step_packed(l, pk[f][l])
+                    ctx.join()
+                torch.cuda.synchronize()
+                best = max(best, 20 / (time.perf_counter() - t0))
+            row[f"frames_per_s_overlap_{mode}"] = round(best, 1)
+            ctx.destroy()
+        rows.append(row)
+    return rows
+
+
 def attend_shapes(torch, xsv, FrameSource, CONFIGS, reps=3):
     """Attention and merge kernel spans (library events on the launch stream, the span of an empty event pair taken
     off) for every workgroup shape and number of key ranges per unit, at the saturated cache of the 24-layer
@@ -270,12 +320,16 @@ def main():
     ap.add_argument("--frames", type=int, default=0, help="frames per workload for --configs (0 = saturation + 12)")
     ap.add_argument("--score-mode", type=int, default=0, choices=(0, 1),
                     help="for --configs: 0 = one retained set per layer (the paper's score), 1 = one per head")
+    ap.add_argument("--value-mode", type=int, default=0, choices=(0, 1),
+                    help="for --configs: 0 = everything re-quantized every step, 1 = values quantized once")
     ap.add_argument("--long", type=int, default=0, help="frames of the long-stream comparison (0 = skip)")
     ap.add_argument("--granularity", action="store_true", help="per-token vs per-channel quantization error table")
     ap.add_argument("--frame-attention", action="store_true", help="time the frame-wise attention entry point")
     ap.add_argument("--selector-sweep", action="store_true", help="output error against an uncompressed cache per variant")
     ap.add_argument("--requant-study", type=int, default=0, metavar="FRAMES",
                     help="fixed points, error drift and the cost of quantizing once, over FRAMES frames of one layer")
+    ap.add_argument("--value-mode-study", action="store_true",
+                    help="re-quantize time and frames/s with values quantized once against re-quantized every step")
     ap.add_argument("--attend-shapes", action="store_true",
                     help="attention / merge time per workgroup shape and number of key ranges (24-layer workload)")
     args = ap.parse_args()
@@ -293,10 +347,11 @@ def main():
         sat = (spec.budget // n + 2) if spec.budget else 2
         frames = args.frames or min(spec.frames, sat + 12)
         rows = run_stream(spec, frames, {frames}, torch, xsv, FrameSource, window=max(1, min(10, frames - sat)),
-                          score_mode=args.score_mode)
+                          score_mode=args.score_mode, value_mode=args.value_mode)
         r = rows[-1]
         print(json.dumps({"workload": spec.name, "layers": spec.n_layers, "tokens_per_frame": n, "budget": spec.budget,
                           "kv_bits": spec.kv_bits, "group_size": spec.group_size, "score_mode": args.score_mode,
+                          "value_mode": args.value_mode,
                           "frames_run": frames,
                           "frames_per_s": round(1e3 / r["ms_per_frame"], 2), **r}), flush=True)
 
@@ -306,6 +361,10 @@ def main():
 
     if args.frame_attention:
         for r in frame_attention(torch, xsv, FrameSource, CONFIGS):
+            print(json.dumps(r), flush=True)
+
+    if args.value_mode_study:
+        for r in value_mode_study(torch, xsv, FrameSource, CONFIGS):
             print(json.dumps(r), flush=True)
 
     if args.attend_shapes:

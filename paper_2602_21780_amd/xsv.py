@@ -31,7 +31,7 @@ class xsv_config(C.Structure):
         ("n_layers", C.c_int32), ("n_heads", C.c_int32), ("head_dim", C.c_int32),
         ("tokens_per_frame", C.c_int32), ("n_special", C.c_int32), ("budget", C.c_int32),
         ("kv_bits", C.c_int32), ("group_size", C.c_int32), ("pool_size", C.c_int32), ("score_mode", C.c_int32),
-        ("softmax_scale", C.c_float), ("max_frames", C.c_int32),
+        ("softmax_scale", C.c_float), ("max_frames", C.c_int32), ("value_mode", C.c_int32),
     ]
 
 
@@ -150,9 +150,9 @@ class Context:
     """Owner of an xsv_ctx.  Method names follow the C entry points."""
 
     def __init__(self, n_layers, n_heads, head_dim, tokens_per_frame, n_special, budget, kv_bits, group_size,
-                 pool_size=16, softmax_scale=0.0, max_frames=0, stream=None, score_mode=0):
+                 pool_size=16, softmax_scale=0.0, max_frames=0, stream=None, score_mode=0, value_mode=0):
         self.cfg = xsv_config(n_layers, n_heads, head_dim, tokens_per_frame, n_special, budget, kv_bits, group_size,
-                              pool_size, score_mode, softmax_scale, max_frames)
+                              pool_size, score_mode, softmax_scale, max_frames, value_mode)
         self._stream = stream
         self._h = C.c_void_p()
         _check(lib().xsv_create(C.byref(self.cfg), _stream_ptr(stream), C.byref(self._h)), "xsv_create")

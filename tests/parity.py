@@ -22,7 +22,8 @@ def make_pair(spec, layers=None, **over):
     L = spec.n_layers if layers is None else len(layers)
     st = ref.RefStream(L, spec.n_heads, spec.head_dim, spec.tokens_per_frame, spec.n_special,
                        over.get("budget", spec.budget), over.get("kv_bits", spec.kv_bits),
-                       over.get("group_size", spec.group_size), spec.pool_size, score_mode=over.get("score_mode", 0))
+                       over.get("group_size", spec.group_size), spec.pool_size, score_mode=over.get("score_mode", 0),
+                       value_mode=over.get("value_mode", 0))
     return ctx, st
 
 

@@ -36,7 +36,7 @@ def test_strerror(lib):
 
 def test_create_rejects_bad_configurations_on_the_host(lib):
     good = dict(n_layers=1, n_heads=2, head_dim=64, tokens_per_frame=64, n_special=5, budget=256, kv_bits=4,
-                group_size=32, pool_size=16, score_mode=0, softmax_scale=0.0, max_frames=0)
+                group_size=32, pool_size=16, score_mode=0, softmax_scale=0.0, max_frames=0, value_mode=0)
     def create(**kw):
         cfg = xsv.xsv_config(**{**good, **kw})
         h = C.c_void_p()
@@ -48,6 +48,7 @@ def test_create_rejects_bad_configurations_on_the_host(lib):
     assert create(n_special=65) == xsv.XSV_ERR_ARG
     assert create(pool_size=0) == xsv.XSV_ERR_ARG
     assert create(score_mode=2) == xsv.XSV_ERR_ARG
+    assert create(value_mode=2) == xsv.XSV_ERR_ARG
     assert create(budget=0, max_frames=0) == xsv.XSV_ERR_ARG
     assert create(head_dim=128) == xsv.XSV_ERR_UNSUPPORTED
     assert create(group_size=16) == xsv.XSV_ERR_UNSUPPORTED

@@ -104,6 +104,40 @@ def test_more_heads_than_one_score_chunk_in_the_papers_mode(bits, G):
     run_stream(spec, 7)
 
 
+@pytest.mark.parametrize("bits,G,H,score_mode", [(4, 64, 3, 0), (4, 32, 2, 0), (2, 64, 5, 0), (2, 32, 3, 1), (4, 64, 4, 1), (16, 64, 2, 0)])
+def test_values_quantized_once(bits, G, H, score_mode):
+    """value_mode 1: a retained value row keeps the codes, scale and zero point of the step that appended it; keys,
+    scores and lists as ever.  Every step against the oracle's variant: caches bit for bit, attention within its
+    tolerance.  (With a bf16 cache the mode changes nothing.)"""
+    spec = CONFIGS[0].with_(name=f"vonce-b{bits}-g{G}-h{H}-m{score_mode}", n_heads=H, tokens_per_frame=150, budget=520,
+                            kv_bits=bits, group_size=G, n_layers=2, seed=37)
+    run_stream(spec, 8, score_mode=score_mode, value_mode=1)
+
+
+def test_values_quantized_once_without_a_budget_and_batched():
+    """The same variant in a cache that is never pruned (one buffer rewritten in place: every old block settles once
+    its keys have, the values are not touched at all), and through the all-layers call at the benchmark's shape."""
+    spec = CONFIGS[0].with_(name="vonce-inplace", n_heads=3, tokens_per_frame=150, budget=0, kv_bits=4, group_size=64,
+                            n_layers=1, seed=39)
+    ctx, st = parity.make_pair(spec, max_frames=9, value_mode=1)
+    src = FrameSource(spec, DEV)
+    for f in range(9):
+        q, k, v = src.frame(f)
+        parity.step_and_compare(ctx, st, spec, 0, 0, q[0], k[0], v[0], budget=0)
+    assert ctx.settled_blocks(0)[0] >= 3 * ((8 * 150) // 64 - 4)
+    ctx.destroy()
+    spec = CONFIGS[2].with_(name="vonce-cfg2", n_layers=2)
+    ctx, st = parity.make_pair(spec, value_mode=1)
+    src = FrameSource(spec, DEV)
+    rows = cover_rows(spec.tokens_per_frame)
+    for f in range(5):
+        q, k, v = src.frame(f)
+        out = ctx.step_all_layers(q, k, v)
+        for l in range(2):
+            parity.step_and_compare(ctx, st, spec, l, l, q[l], k[l], v[l], rows=rows, stepped=True, out_gpu=out[l])
+    ctx.destroy()
+
+
 def test_per_head_selection_batched_equals_per_layer_steps():
     spec = CONFIGS[0].with_(name="perhead-batched", n_layers=3, n_heads=4, tokens_per_frame=150, budget=400, group_size=64, seed=19)
     ctx_a = xsv.Context.from_spec(spec, score_mode=1)
