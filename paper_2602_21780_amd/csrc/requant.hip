@@ -77,7 +77,8 @@ __device__ __forceinline__ uint32_t quant_code(float x, float s, float z, int bi
   return (uint32_t)q;
 }
 
-template <int BITS, int G>
+// CARRY: RequantArgs::carry_values as a compile-time property (the default path carries no trace of the variant)
+template <int BITS, int G, bool CARRY = false>
 __global__ __launch_bounds__(256) void requant_kernel(const RequantArgs a) {
   constexpr bool kQuant = BITS != 16;
   constexpr int kRowDw = kD * BITS / 32;  // dwords per packed key row / value block row
@@ -259,8 +260,8 @@ __global__ __launch_bounds__(256) void requant_kernel(const RequantArgs a) {
   // ---------------- values ----------------
   // "quantize once" (carry_values): a row that comes from the cache keeps its codes and parameters; a wave whose rows
   // all do skips the arithmetic altogether
-  const bool carry = kQuant && a.carry_values && from_cache;
-  const bool all_carried = kQuant && a.carry_values && __all(from_cache || !row_valid);
+  const bool carry = kQuant && CARRY && from_cache;
+  const bool all_carried = kQuant && CARRY && __all(from_cache || !row_valid);
 #pragma unroll
   for (int e = 0; e < 16; ++e) x[e] = 0.f;
   if (from_cache && !all_carried) {
@@ -374,11 +375,16 @@ hipError_t launch_requant(const RequantArgs& a, hipStream_t stream) {
   if (a.Tn <= 0) return hipSuccess;
   const dim3 grid((a.Tn + kTile - 1) / kTile, a.pool.H, a.b.n_layers);
   const int bits = a.pool.bits, G = a.pool.G;
+  const bool carry = a.carry_values != 0 && bits != 16;
   if (bits == 16) hipLaunchKernelGGL((requant_kernel<16, 64>), grid, dim3(256), 0, stream, a);
-  else if (bits == 4 && G == 64) hipLaunchKernelGGL((requant_kernel<4, 64>), grid, dim3(256), 0, stream, a);
-  else if (bits == 4 && G == 32) hipLaunchKernelGGL((requant_kernel<4, 32>), grid, dim3(256), 0, stream, a);
-  else if (bits == 2 && G == 64) hipLaunchKernelGGL((requant_kernel<2, 64>), grid, dim3(256), 0, stream, a);
-  else if (bits == 2 && G == 32) hipLaunchKernelGGL((requant_kernel<2, 32>), grid, dim3(256), 0, stream, a);
+  else if (bits == 4 && G == 64 && !carry) hipLaunchKernelGGL((requant_kernel<4, 64>), grid, dim3(256), 0, stream, a);
+  else if (bits == 4 && G == 32 && !carry) hipLaunchKernelGGL((requant_kernel<4, 32>), grid, dim3(256), 0, stream, a);
+  else if (bits == 2 && G == 64 && !carry) hipLaunchKernelGGL((requant_kernel<2, 64>), grid, dim3(256), 0, stream, a);
+  else if (bits == 2 && G == 32 && !carry) hipLaunchKernelGGL((requant_kernel<2, 32>), grid, dim3(256), 0, stream, a);
+  else if (bits == 4 && G == 64) hipLaunchKernelGGL((requant_kernel<4, 64, true>), grid, dim3(256), 0, stream, a);
+  else if (bits == 4 && G == 32) hipLaunchKernelGGL((requant_kernel<4, 32, true>), grid, dim3(256), 0, stream, a);
+  else if (bits == 2 && G == 64) hipLaunchKernelGGL((requant_kernel<2, 64, true>), grid, dim3(256), 0, stream, a);
+  else if (bits == 2 && G == 32) hipLaunchKernelGGL((requant_kernel<2, 32, true>), grid, dim3(256), 0, stream, a);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }
