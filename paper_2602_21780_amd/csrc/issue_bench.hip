@@ -204,6 +204,7 @@ __global__ __launch_bounds__(512) void tile_loop(unsigned long long* out, float*
     __builtin_amdgcn_sched_barrier(0);
   };
   __syncthreads();
+  const unsigned long long r0 = __builtin_amdgcn_s_memrealtime();
   const unsigned long long t0 = now();
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
@@ -221,6 +222,7 @@ __global__ __launch_bounds__(512) void tile_loop(unsigned long long* out, float*
   }
   const unsigned long long t1 = now();
   if ((threadIdx.x & 63) == 0) out[blockIdx.x * 16 + (threadIdx.x >> 6)] = t1 - t0;
+  if (threadIdx.x == 0) out[256 * 16 + blockIdx.x] = __builtin_amdgcn_s_memrealtime() - r0;  // 100 MHz wall clock
   float acc = l[0] + l[1];
   for (int i = 0; i < 16; ++i) acc += o0[0][i] + o0[1][i] + o1[0][i] + o1[1][i] + sA[i] + sB[i];
   sink[blockIdx.x * blockDim.x + threadIdx.x] = acc;
@@ -239,10 +241,12 @@ void run_tile(const char* name, int threads, unsigned long long* dout, float* si
   (void)hipDeviceSynchronize();
   float ms = 0.f;
   (void)hipEventElapsedTime(&ms, e0, e1);
-  std::vector<unsigned long long> h(blocks * 16);
+  std::vector<unsigned long long> h(blocks * 17);
   if (hipMemcpy(h.data(), dout, h.size() * 8, hipMemcpyDeviceToHost) != hipSuccess) { printf("copy failed\n"); return; }
-  printf("%-44s waves/SIMD %d: wave 0 %7.1f cycles per tile; launch %7.1f ns per tile\n", name, threads / 256, (double)h[0] / iters,
-         ms * 1e6 / iters);
+  // shader clock of workgroup 0 while the loop ran: its cycle count over its 100 MHz wall-clock count
+  const double mhz = (double)h[0] / ((double)h[blocks * 16] / 100.0);
+  printf("%-44s waves/SIMD %d: wave 0 %7.1f cycles per tile; launch %7.1f ns per tile; shader clock %4.0f MHz\n", name, threads / 256,
+         (double)h[0] / iters, ms * 1e6 / iters, mhz);
 }
 
 template <int MODE>
@@ -269,7 +273,7 @@ void run(const char* name, int per_iter, int threads, unsigned long long* dout, 
 
 int main() {
   unsigned long long* dout; float* sink;
-  if (hipMalloc(&dout, 256 * 16 * 8) != hipSuccess || hipMalloc(&sink, 256 * 1024 * 4) != hipSuccess) { printf("no device memory\n"); return 1; }
+  if (hipMalloc(&dout, 256 * 17 * 8) != hipSuccess || hipMalloc(&sink, 256 * 1024 * 4) != hipSuccess) { printf("no device memory\n"); return 1; }
   for (int threads : {256, 512, 768, 1024}) {
     run<0>("64 fma (8 chains)", 64, threads, dout, sink);
     run<1>("64 exp (8 chains)", 64, threads, dout, sink);
