@@ -53,6 +53,14 @@ int xsv_last_attend_workgroups(xsv_ctx* ctx, int32_t* workgroups);
  * of 512 (e.g. 1041 tokens).  Other values: XSV_ERR_ARG.  Results agree to rounding. */
 int xsv_set_attend_variant(xsv_ctx* ctx, int variant);
 
+/* Host only (no GPU call): where the attention launch of a step cuts a (head, query block)'s key tiles - `cache_tiles`
+ * tiles of 64 cached tokens followed by `frame_tiles` tiles of the frame's own tokens - into `ranges` consecutive key
+ * ranges of equal cost, a frame tile costing `frame_tile_cost` percent of a cache tile and the last range
+ * `last_percent` percent of a full share.  begin[0] = 0 <= begin[1] < .. < begin[ranges] = all tiles; every range holds
+ * at least one tile.  1 <= ranges <= min(16, tiles), 1 <= last_percent <= 100, 25 <= frame_tile_cost <= 400, else
+ * XSV_ERR_ARG.  For tests and for sizing experiments; the library calls the same routine. */
+int xsv_key_ranges(int cache_tiles, int frame_tiles, int ranges, int last_percent, int frame_tile_cost, int32_t* begin);
+
 /* Measurement aid, synchronous.  The re-quantization leaves out blocks of 64 cached tokens that keep their place
  * (the first frame's, or all old blocks of a cache that is not pruned) once re-quantizing them has reproduced them
  * bit for bit: `settled` = (head, block) pairs of the layer in that state, `total` = (head, block) pairs it holds. */

@@ -688,6 +688,14 @@ int xsv_set_side_cus(xsv_ctx* ctx, int compute_units) {
   return XSV_OK;
 }
 
+int xsv_key_ranges(int cache_tiles, int frame_tiles, int ranges, int last_percent, int frame_tile_cost, int32_t* begin) {
+  if (!begin || cache_tiles < 0 || frame_tiles < 0 || ranges < 1 || ranges > kMaxPieces || ranges > cache_tiles + frame_tiles ||
+      last_percent < 1 || last_percent > 100 || frame_tile_cost < 25 || frame_tile_cost > 400)
+    return XSV_ERR_ARG;
+  range_starts(cache_tiles, frame_tiles, ranges, last_percent, frame_tile_cost, begin);
+  return XSV_OK;
+}
+
 int xsv_set_attend_variant(xsv_ctx* ctx, int variant) {
   if (!ctx || variant < 0 || variant > 3) return XSV_ERR_ARG;
   ctx->attend_variant = variant;

@@ -50,6 +50,7 @@ EXPORTS = (
 TUNE_EXPORTS = (
     "xsv_set_attend_splits", "xsv_set_attend_variant", "xsv_set_side_cus", "xsv_set_short_range", "xsv_set_frame_tile_cost",
     "xsv_last_attend_workgroups", "xsv_settled_blocks", "xsv_set_attend_timing", "xsv_attend_times", "xsv_chain_times", "xsv_measure_peaks",
+    "xsv_key_ranges",
 )
 
 _lib = None
@@ -378,6 +379,13 @@ def topk_keep(scores, k, T_first, T_cur, stream=None):
     _check(lib().xsv_topk_keep(_stream_ptr(stream), scores.data_ptr() if P else None, P, k, T_first, T_cur,
                                keep.data_ptr()), "xsv_topk_keep")
     return keep
+
+
+def key_ranges(cache_tiles, frame_tiles, ranges, last_percent=100, frame_tile_cost=95):
+    """xsv_key_ranges (host only): the tile index at which each of `ranges` key ranges begins, plus the total."""
+    begin = (C.c_int32 * (ranges + 1))()
+    _check(lib().xsv_key_ranges(cache_tiles, frame_tiles, ranges, last_percent, frame_tile_cost, begin), "xsv_key_ranges")
+    return list(begin)
 
 
 def measure_peaks(stream=None):

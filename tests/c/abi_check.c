@@ -21,7 +21,7 @@ int main(void) {
                          /* xsv_tune.h */
                          (fn)xsv_set_attend_splits, (fn)xsv_set_attend_variant, (fn)xsv_set_side_cus,
                          (fn)xsv_set_short_range, (fn)xsv_set_frame_tile_cost, (fn)xsv_last_attend_workgroups, (fn)xsv_settled_blocks, (fn)xsv_set_attend_timing,
-                         (fn)xsv_attend_times, (fn)xsv_chain_times, (fn)xsv_measure_peaks};
+                         (fn)xsv_attend_times, (fn)xsv_chain_times, (fn)xsv_measure_peaks, (fn)xsv_key_ranges};
   size_t i;
   memset(&cfg, 0, sizeof cfg);
   memset(&t, 0, sizeof t);
@@ -33,6 +33,7 @@ int main(void) {
   if (xsv_destroy(NULL) != XSV_OK) return 5;
   if (xsv_set_attend_splits(NULL, 0, 0) != XSV_ERR_ARG) return 6;
   if (xsv_measure_peaks(NULL, NULL, NULL) != XSV_ERR_ARG) return 7;
+  if (xsv_key_ranges(64, 22, 5, 50, 95, NULL) != XSV_ERR_ARG) return 8;
   printf("abi ok: %u entry points, config %u bytes, tensor %u bytes\n", (unsigned)(sizeof entry / sizeof entry[0]),
          (unsigned)sizeof cfg, (unsigned)sizeof t);
   return 0;

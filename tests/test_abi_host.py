@@ -93,3 +93,33 @@ def test_header_compiles_as_c_and_every_entry_point_links(tmp_path):
     assert r.returncode == 0, r.stderr
     r = subprocess.run([exe], capture_output=True, text=True)
     assert r.returncode == 0 and "abi ok" in r.stdout, (r.returncode, r.stdout, r.stderr)
+
+
+def test_key_ranges_cover_the_tiles_with_equal_cost(lib):
+    """The host routine that places the key ranges of an attention launch: the ranges tile [0, tiles) without gaps,
+    none is empty, the full ranges cost the same to within one tile, and a short last range costs about its share."""
+    import itertools
+    for n_ct, n_ft, R, pct, fc in itertools.product((0, 1, 7, 64, 129, 1000), (1, 17, 22), (1, 2, 3, 5, 8, 16), (100, 50, 35, 1),
+                                                    (25, 95, 100, 160, 400)):
+        tiles = n_ct + n_ft
+        if R > tiles:
+            assert lib.xsv_key_ranges(n_ct, n_ft, R, pct, fc, (C.c_int32 * (R + 1))()) == xsv.XSV_ERR_ARG
+            continue
+        b = xsv.key_ranges(n_ct, n_ft, R, pct, fc)
+        assert b[0] == 0 and b[-1] == tiles and all(x < y for x, y in zip(b, b[1:])), (n_ct, n_ft, R, pct, fc, b)
+        cost = lambda t0, t1: sum(100 if t < n_ct else fc for t in range(t0, t1))
+        costs = [cost(b[i], b[i + 1]) for i in range(R)]
+        total = sum(costs)
+        share = total * 100.0 / (100 * (R - 1) + pct)             # cost of a full range
+        biggest = max(100, fc)
+        if R > 1 and tiles >= 4 * R:                              # (with very few tiles "one tile each" takes over)
+            # (a last range that must hold one whole tile although its share is smaller takes the excess from the others)
+            slack = biggest + max(0.0, (100 if tiles - 1 < n_ct else fc) - share * pct / 100.0)
+            for c in costs[:-1]:
+                assert abs(c - share) <= slack, (n_ct, n_ft, R, pct, fc, b, costs)
+            assert abs(costs[-1] - share * pct / 100.0) <= biggest * (R - 1) / 2 + biggest, (n_ct, n_ft, R, pct, fc, b, costs)
+    # the benchmark's cut: 64 cache + 22 frame tiles, four long ranges and a half one
+    b = xsv.key_ranges(64, 22, 5, 50, 95)
+    assert b == sorted(b) and b[-1] == 86 and 17 <= b[1] <= 20 and b[4] - b[3] >= b[5] - b[4]
+    for bad in ((-1, 5, 2, 100, 95), (5, 5, 0, 100, 95), (5, 5, 17, 100, 95), (5, 5, 2, 0, 95), (5, 5, 2, 101, 95), (5, 5, 2, 100, 24)):
+        assert lib.xsv_key_ranges(*bad, (C.c_int32 * 18)()) == xsv.XSV_ERR_ARG
