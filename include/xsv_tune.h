@@ -61,6 +61,13 @@ int xsv_set_attend_variant(xsv_ctx* ctx, int variant);
  * XSV_ERR_ARG.  For tests and for sizing experiments; the library calls the same routine. */
 int xsv_key_ranges(int cache_tiles, int frame_tiles, int ranges, int last_percent, int frame_tile_cost, int32_t* begin);
 
+/* Host only: the other way an attention launch divides its work, used when the workgroup count is not a multiple of
+ * the units - the `units * tiles` (unit, key tile) items in one line, cut into `workgroups` pieces that differ by at
+ * most one item.  Piece `workgroup` is [*begin, *end); unit `unit` is touched by workgroups *first .. *last.  Any
+ * pointer may be NULL.  units, tiles, workgroups >= 1, 0 <= workgroup < workgroups, 0 <= unit < units, else XSV_ERR_ARG. */
+int xsv_line_partition(int64_t units, int tiles, int workgroups, int workgroup, int64_t* begin, int64_t* end, int64_t unit,
+                       int32_t* first, int32_t* last);
+
 /* Measurement aid, synchronous.  The re-quantization leaves out blocks of 64 cached tokens that keep their place
  * (the first frame's, or all old blocks of a cache that is not pruned) once re-quantizing them has reproduced them
  * bit for bit: `settled` = (head, block) pairs of the layer in that state, `total` = (head, block) pairs it holds. */

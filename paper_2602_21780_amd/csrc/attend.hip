@@ -843,6 +843,18 @@ static hipError_t launch_attend_v(const AttendArgs& a, hipStream_t stream, hipEv
   }
 }
 
+// Host-side queries of the partition the kernel uses when the units are not all cut alike (for tests).
+void partition_query(long long n_units, int n_tiles, int n_wgs, int wg, long long* begin, long long* end) {
+  const Partition part{n_units * n_tiles, n_tiles, n_wgs};
+  *begin = part.begin(wg);
+  *end = part.begin(wg + 1);
+}
+void partition_unit_query(long long n_units, int n_tiles, int n_wgs, int unit, int* first_wg, int* last_wg) {
+  const Partition part{n_units * n_tiles, n_tiles, n_wgs};
+  *first_wg = part.first_wg(unit);
+  *last_wg = part.last_wg(unit);
+}
+
 int attend_rows_per_workgroup(int variant) {
   return variant == 1 ? 128 : (variant == 3 ? 512 : 256);
 }

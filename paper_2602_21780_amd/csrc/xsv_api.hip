@@ -696,6 +696,22 @@ int xsv_key_ranges(int cache_tiles, int frame_tiles, int ranges, int last_percen
   return XSV_OK;
 }
 
+int xsv_line_partition(int64_t units, int tiles, int workgroups, int workgroup, int64_t* begin, int64_t* end, int64_t unit,
+                       int32_t* first, int32_t* last) {
+  if (units < 1 || tiles < 1 || workgroups < 1 || workgroup < 0 || workgroup >= workgroups || unit < 0 || unit >= units ||
+      units > (1ll << 40) / tiles)
+    return XSV_ERR_ARG;
+  long long b = 0, e = 0;
+  int f = 0, l = 0;
+  partition_query(units, tiles, workgroups, workgroup, &b, &e);
+  partition_unit_query(units, tiles, workgroups, (int)unit, &f, &l);
+  if (begin) *begin = b;
+  if (end) *end = e;
+  if (first) *first = f;
+  if (last) *last = l;
+  return XSV_OK;
+}
+
 int xsv_set_attend_variant(xsv_ctx* ctx, int variant) {
   if (!ctx || variant < 0 || variant > 3) return XSV_ERR_ARG;
   ctx->attend_variant = variant;

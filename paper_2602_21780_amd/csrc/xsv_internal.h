@@ -152,6 +152,8 @@ struct AttendPlan {
 // Chooses the grid: at most want_wgs workgroups, pieces of at least 4 tiles, and no unit shared by
 // more workgroups than the partial workspace (part_rows rows) and the merge can hold.
 AttendPlan plan_attend(int variant, int n_layers, int H, int n, int Tc, int want_wgs, size_t part_rows);
+void partition_query(long long n_units, int n_tiles, int n_wgs, int wg, long long* begin, long long* end);
+void partition_unit_query(long long n_units, int n_tiles, int n_wgs, int unit, int* first_wg, int* last_wg);
 // `between` (optional): an event recorded after the attention kernel, before the merge kernel.
 hipError_t launch_attend(const AttendArgs& a, hipStream_t stream, hipEvent_t between = nullptr);
 int attend_rows_per_workgroup(int variant);

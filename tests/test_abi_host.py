@@ -123,3 +123,27 @@ def test_key_ranges_cover_the_tiles_with_equal_cost(lib):
     assert b == sorted(b) and b[-1] == 86 and 17 <= b[1] <= 20 and b[4] - b[3] >= b[5] - b[4]
     for bad in ((-1, 5, 2, 100, 95), (5, 5, 0, 100, 95), (5, 5, 17, 100, 95), (5, 5, 2, 0, 95), (5, 5, 2, 101, 95), (5, 5, 2, 100, 24)):
         assert lib.xsv_key_ranges(*bad, (C.c_int32 * 18)()) == xsv.XSV_ERR_ARG
+
+
+def test_line_partition_is_a_partition(lib):
+    """The (unit, tile) line cut into workgroup pieces: the pieces tile the line in order, differ by at most one item,
+    and the workgroups that touch a unit are exactly those whose piece overlaps it."""
+    lib.xsv_line_partition.argtypes = [C.c_int64, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int64), C.POINTER(C.c_int64),
+                                       C.c_int64, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+    for units, tiles, wgs in ((48, 86, 224), (48, 86, 256), (1152, 86, 256), (3, 1, 5), (7, 3, 4), (1, 1, 1), (5, 9, 45), (5, 9, 44)):
+        b, e = C.c_int64(), C.c_int64()
+        pieces = []
+        for w in range(wgs):
+            assert lib.xsv_line_partition(units, tiles, wgs, w, C.byref(b), C.byref(e), 0, None, None) == xsv.XSV_OK
+            pieces.append((b.value, e.value))
+        assert pieces[0][0] == 0 and pieces[-1][1] == units * tiles
+        assert all(p[1] == q[0] for p, q in zip(pieces, pieces[1:]))
+        sizes = [p[1] - p[0] for p in pieces]
+        assert max(sizes) - min(sizes) <= 1 and min(sizes) >= 0
+        f, l = C.c_int32(), C.c_int32()
+        for u in range(units):
+            assert lib.xsv_line_partition(units, tiles, wgs, 0, None, None, u, C.byref(f), C.byref(l)) == xsv.XSV_OK
+            touching = [w for w, (p0, p1) in enumerate(pieces) if p0 < (u + 1) * tiles and p1 > u * tiles]
+            assert (f.value, l.value) == (touching[0], touching[-1]), (units, tiles, wgs, u)
+    assert lib.xsv_line_partition(0, 1, 1, 0, None, None, 0, None, None) == xsv.XSV_ERR_ARG
+    assert lib.xsv_line_partition(4, 4, 4, 4, None, None, 0, None, None) == xsv.XSV_ERR_ARG
