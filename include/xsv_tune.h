@@ -68,6 +68,13 @@ int xsv_key_ranges(int cache_tiles, int frame_tiles, int ranges, int last_percen
 int xsv_line_partition(int64_t units, int tiles, int workgroups, int workgroup, int64_t* begin, int64_t* end, int64_t unit,
                        int32_t* first, int32_t* last);
 
+/* Host only: what one step does to a cache of `cache_tokens` tokens that has seen `frames_seen` frames, under this
+ * configuration (token counting of Sec. 3.2: nothing is pruned while the cache plus the frame fit the budget or on
+ * the first frame; otherwise the middle of *middle tokens keeps its *keep best ones beside the first and the current
+ * frame).  *new_len = cache length after the step.  Any pointer may be NULL.  The library's own step uses the same
+ * routine.  cfg NULL or invalid counts: XSV_ERR_ARG. */
+int xsv_step_plan(const xsv_config* cfg, int cache_tokens, int frames_seen, int32_t* middle, int32_t* keep, int32_t* new_len);
+
 /* Measurement aid, synchronous.  The re-quantization leaves out blocks of 64 cached tokens that keep their place
  * (the first frame's, or all old blocks of a cache that is not pruned) once re-quantizing them has reproduced them
  * bit for bit: `settled` = (head, block) pairs of the layer in that state, `total` = (head, block) pairs it holds. */

@@ -696,6 +696,18 @@ int xsv_key_ranges(int cache_tiles, int frame_tiles, int ranges, int last_percen
   return XSV_OK;
 }
 
+int xsv_step_plan(const xsv_config* cfg, int cache_tokens, int frames_seen, int32_t* middle, int32_t* keep, int32_t* new_len) {
+  if (!cfg || cfg->tokens_per_frame < 1 || cfg->budget < 0 || cache_tokens < 0 || frames_seen < 0) return XSV_ERR_ARG;
+  LayerState L;
+  L.T = cache_tokens;
+  L.frames = frames_seen;
+  const PrunePlan p = plan_for(*cfg, L);
+  if (middle) *middle = p.P;
+  if (keep) *keep = p.k;
+  if (new_len) *new_len = p.Tn;
+  return XSV_OK;
+}
+
 int xsv_line_partition(int64_t units, int tiles, int workgroups, int workgroup, int64_t* begin, int64_t* end, int64_t unit,
                        int32_t* first, int32_t* last) {
   if (units < 1 || tiles < 1 || workgroups < 1 || workgroup < 0 || workgroup >= workgroups || unit < 0 || unit >= units ||

@@ -50,7 +50,7 @@ EXPORTS = (
 TUNE_EXPORTS = (
     "xsv_set_attend_splits", "xsv_set_attend_variant", "xsv_set_side_cus", "xsv_set_short_range", "xsv_set_frame_tile_cost",
     "xsv_last_attend_workgroups", "xsv_settled_blocks", "xsv_set_attend_timing", "xsv_attend_times", "xsv_chain_times", "xsv_measure_peaks",
-    "xsv_key_ranges", "xsv_line_partition",
+    "xsv_key_ranges", "xsv_line_partition", "xsv_step_plan",
 )
 
 _lib = None

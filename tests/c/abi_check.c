@@ -21,7 +21,7 @@ int main(void) {
                          /* xsv_tune.h */
                          (fn)xsv_set_attend_splits, (fn)xsv_set_attend_variant, (fn)xsv_set_side_cus,
                          (fn)xsv_set_short_range, (fn)xsv_set_frame_tile_cost, (fn)xsv_last_attend_workgroups, (fn)xsv_settled_blocks, (fn)xsv_set_attend_timing,
-                         (fn)xsv_attend_times, (fn)xsv_chain_times, (fn)xsv_measure_peaks, (fn)xsv_key_ranges, (fn)xsv_line_partition};
+                         (fn)xsv_attend_times, (fn)xsv_chain_times, (fn)xsv_measure_peaks, (fn)xsv_key_ranges, (fn)xsv_line_partition, (fn)xsv_step_plan};
   size_t i;
   memset(&cfg, 0, sizeof cfg);
   memset(&t, 0, sizeof t);

@@ -147,3 +147,31 @@ def test_line_partition_is_a_partition(lib):
             assert (f.value, l.value) == (touching[0], touching[-1]), (units, tiles, wgs, u)
     assert lib.xsv_line_partition(0, 1, 1, 0, None, None, 0, None, None) == xsv.XSV_ERR_ARG
     assert lib.xsv_line_partition(4, 4, 4, 4, None, None, 0, None, None) == xsv.XSV_ERR_ARG
+
+
+def test_step_plan_follows_the_oracles_cache_lengths(lib, ref):
+    """The library's token counting against the oracle stepped on real frames: the same cache length after every step
+    (64, 128, 192, 256, 256, .. at the tiny configuration), the same number of kept middle tokens, also where the
+    budget is below two frames (k = 0) and without a budget."""
+    import numpy as np
+    from paper_2602_21780_amd.inputs import CONFIGS, FrameSource, to_u16
+    for budget in (256, 200, 100, 0, 64 * 5 + 7):
+        spec = CONFIGS[0].with_(budget=budget, n_heads=1)
+        cfg = xsv.xsv_config(1, 1, 64, spec.tokens_per_frame, spec.n_special, budget, 4, 32, spec.pool_size, 0, 0.0, 9, 0)
+        st = ref.RefStream(1, 1, 64, spec.tokens_per_frame, spec.n_special, budget, 4, 32, spec.pool_size)
+        src = FrameSource(spec, "cpu", layers=[0])
+        T = 0
+        for f in range(8):
+            q, k, v = (to_u16(t[0]) for t in src.frame(f))
+            mid, keep, new = C.c_int32(), C.c_int32(), C.c_int32()
+            assert lib.xsv_step_plan(C.byref(cfg), T, f, C.byref(mid), C.byref(keep), C.byref(new)) == xsv.XSV_OK
+            _, T_ref = st.step(0, q, k, v, attend=False)
+            assert new.value == T_ref, (budget, f, new.value, T_ref)
+            n = spec.tokens_per_frame
+            if mid.value:                                            # a pruning step: first + kept middle + current
+                assert new.value == n + keep.value + n and mid.value == T + n - 2 * n
+                assert keep.value == min(max(0, budget - 2 * n), mid.value)
+            T = new.value
+        if budget:
+            assert T <= max(budget, 2 * spec.tokens_per_frame)
+    assert lib.xsv_step_plan(None, 0, 0, None, None, None) == xsv.XSV_ERR_ARG
